@@ -1,0 +1,129 @@
+/*
+ * hipattn - Hierarchically Pruned Attention (HiP) hot path for AMD MI355X (gfx950).
+ *
+ * C ABI of the two operations of the paper's problem statement:
+ *
+ *   hip_mask_estimate : hierarchical top-k key estimation
+ *                       (paper Sec. 3.1 "Hierarchical Score-Locality-Aware Top-k Estimation",
+ *                        Sec. 3.2 "Block Approximation", Alg. 1; per-step use in Alg. 2)
+ *   hip_sparse_attn   : block-sparse attention over the selected keys
+ *                       (paper Eq. 1-3; "Block Sparse Flash Attention" in the appendix)
+ *
+ * NOTE ON NAMES: "hip_" / "HIP_" here abbreviates the method (HiP attention), not the
+ * GPU runtime whose symbols are spelled hipXxx.
+ *
+ * General rules for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees, copies to the host or synchronises; a call validates its
+ *     arguments on the host and enqueues kernels on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).  Results are ready when the stream reaches them.
+ *   - `hip_problem` itself is read on the host during the call and may be freed afterwards;
+ *     the arrays it points to (kv_lens, page_table) are DEVICE arrays read by the kernels.
+ *   - Return value: HIP_ATTN_OK (0), a negative HIP_ATTN_E* argument error detected before
+ *     any launch, or HIP_ATTN_ELAUNCH - (hipError_t) for a failed launch.  Nothing is
+ *     printed; NaN/Inf inputs give unspecified indices.
+ *   - Re-entrant; no mutable global state.
+ *
+ * Conventions (0-based):
+ *   kb      = k / bk                       key blocks kept per query block
+ *   g       = n_q_heads / n_kv_heads       query head h reads KV head h / g
+ *   pos(i)  = kv_len - q_len + i           absolute position of query row i of a sequence
+ *   query block qb = rows [qb*bq, min((qb+1)*bq, q_len)); it searches the key blocks of
+ *   its visible prefix [0, min(kv_len, pos(last row)+1)).
+ */
+#ifndef HIPATTN_H
+#define HIPATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HIP_ATTN_SENTINEL INT32_MAX /* "no block" entry of the index array */
+
+enum {
+    HIP_ATTN_OK = 0,
+    HIP_ATTN_ENULL = -1,       /* a required pointer is NULL                                  */
+    HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len   */
+    HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1    */
+    HIP_ATTN_EHEADDIM = -4,    /* head_dim not in {64, 128}                                   */
+    HIP_ATTN_EDTYPE = -5,      /* dtype not HIP_ATTN_F32 / HIP_ATTN_BF16                      */
+    HIP_ATTN_ETOOLARGE = -6,   /* k/bk above HIP_ATTN_MAX_KB, or bq*head_dim above the limit  */
+    HIP_ATTN_EALIGN = -7,      /* a pointer or row stride is not 16-byte aligned              */
+    HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0 */
+    HIP_ATTN_ELAUNCH = -1000   /* launch failure: code is HIP_ATTN_ELAUNCH - hipError_t       */
+};
+
+enum { HIP_ATTN_F32 = 0, HIP_ATTN_BF16 = 1 };
+
+/* flags */
+enum {
+    HIP_ATTN_FORCE_GENERIC = 1 /* use the shape-generic kernels even where a tuned one exists */
+};
+
+#define HIP_ATTN_MAX_KB 1024   /* largest k/bk                                                */
+#define HIP_ATTN_MAX_BQ 64     /* largest query block                                         */
+#define HIP_ATTN_MAX_BK 16     /* largest key block                                           */
+
+typedef struct hip_problem {
+    int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64,128}                     */
+    int32_t q_len;       /* query rows per sequence: T for prefill, 1 for decode               */
+    int32_t max_kv_len;  /* T of contiguous K/V, or the largest kv_lens[b]                     */
+    int32_t k, bq, bk;   /* k % bk == 0; 1 <= bq <= 64; 1 <= bk <= 16                          */
+    int32_t dtype;       /* HIP_ATTN_F32 or HIP_ATTN_BF16; Q, K, V, O all have this type       */
+    int32_t flags;       /* HIP_ATTN_FORCE_GENERIC or 0                                        */
+    float sm_scale;      /* softmax scale of hip_sparse_attn; <= 0 selects 1/sqrt(head_dim)    */
+    const int32_t *kv_lens;    /* device [batch], q_len <= kv_lens[b] <= max_kv_len; NULL = max_kv_len */
+    const int32_t *page_table; /* device [batch, max_pages] or NULL (contiguous K/V)           */
+    int32_t page_size, max_pages; /* tokens per page (multiple of bk); row length of the table */
+    /* Element strides (batch, head, row); the channel dimension is contiguous.  All zero =
+     * dense row-major: Q,O [batch, n_q_heads, q_len, head_dim]; K,V [batch, n_kv_heads,
+     * max_kv_len, head_dim], or with a page table the pool [n_pages, n_kv_heads, page_size,
+     * head_dim] where kv_strides[0] is the page stride.  Row strides must keep rows 16-byte
+     * aligned. */
+    int64_t q_strides[3], kv_strides[3], o_strides[3];
+} hip_problem;
+
+/*
+ * Hierarchical mask estimation (Alg. 1 with the block form of Sec. 3.2).
+ *   Q        device, layout per q_strides
+ *   K        device, layout per kv_strides (sequence-major, or the page pool)
+ *   indices  device int32 [batch, n_q_heads, ceil(q_len/bq), k/bk], written by the call:
+ *            row (b,h,qb,:) holds the first logical token position (a multiple of bk) of each
+ *            selected key block, strictly ascending, followed by HIP_ATTN_SENTINEL padding
+ *            when fewer than k/bk blocks are visible.  Positions are logical (before page
+ *            translation).
+ * Scores are unscaled dot products accumulated in fp32; the score of a branch is the maximum
+ * over the query block's rows and the representative (centre) key block's keys of the
+ * causally admissible products; equal scores are resolved towards the lower position.
+ */
+int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_t *indices,
+                      void *stream);
+
+/*
+ * Block-sparse attention (Eq. 2-3 with the mask given by `indices`).
+ *   indices  as written by hip_mask_estimate; any entry < 0 or >= kv_len means "no block";
+ *            valid entries of a row must be distinct.
+ *   O        device, layout per o_strides, same dtype as Q.  Row i attends to the keys t of
+ *            its query block's selected blocks with t < kv_len and t <= pos(i); a row with no
+ *            such key is written as zeros.  Softmax statistics and accumulation are fp32.
+ */
+int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const void *V,
+                    const int32_t *indices, void *O, void *stream);
+
+/* Device scratch the two calls need for this problem (always 0 in this version: the
+ * kernels keep their state in LDS and registers). */
+size_t hip_workspace_bytes(const hip_problem *p);
+
+/* Static, human-readable text for a return code. */
+const char *hip_strerror(int code);
+
+/* Library version, major*100 + minor. */
+int hip_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIPATTN_H */

@@ -1,0 +1,152 @@
+"""Thin ctypes binding of libhipattn.so: argument marshalling only.
+
+Every step of the method runs in the library's HIP kernels; torch tensors are used for
+device memory and the current stream.  There is no CPU or eager fallback: if the shared
+library is missing or a tensor is not on a GPU the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhipattn.so")
+SENTINEL = 2**31 - 1
+F32, BF16 = 0, 1
+FORCE_GENERIC = 1
+
+EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
+
+
+class HipProblem(ctypes.Structure):
+    """Mirror of `hip_problem` in include/hipattn.h."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("q_len", ctypes.c_int32), ("max_kv_len", ctypes.c_int32),
+        ("k", ctypes.c_int32), ("bq", ctypes.c_int32), ("bk", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+        ("kv_lens", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
+        ("q_strides", ctypes.c_int64 * 3), ("kv_strides", ctypes.c_int64 * 3), ("o_strides", ctypes.c_int64 * 3),
+    ]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library (build it first with `python -m paper_2406_09827_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.hip_mask_estimate.restype = ctypes.c_int
+        lib.hip_mask_estimate.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p]
+        lib.hip_sparse_attn.restype = ctypes.c_int
+        lib.hip_sparse_attn.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.hip_workspace_bytes.restype = ctypes.c_size_t
+        lib.hip_workspace_bytes.argtypes = [ctypes.POINTER(HipProblem)]
+        lib.hip_strerror.restype = ctypes.c_char_p
+        lib.hip_strerror.argtypes = [ctypes.c_int]
+        lib.hip_attn_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+class HipAttnError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"hipattn error {code}: {load().hip_strerror(code).decode()}")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _need_gpu(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise RuntimeError("hipattn needs device tensors (no CPU path exists)")
+
+
+def make_problem(Q: torch.Tensor, K: torch.Tensor, k: int, bq: int, bk: int,
+                 kv_lens: Optional[torch.Tensor] = None, page_table: Optional[torch.Tensor] = None,
+                 max_kv_len: Optional[int] = None, sm_scale: float = 0.0, flags: int = 0,
+                 O: Optional[torch.Tensor] = None) -> HipProblem:
+    """Describe a call from tensor shapes/strides.  Q [B,Hq,Tq,d]; K [B,Hkv,T,d] or, with a
+    page table, the pool [n_pages,Hkv,page,d]."""
+    assert Q.dim() == 4 and K.dim() == 4 and Q.stride(3) == 1 and K.stride(3) == 1
+    p = HipProblem()
+    p.batch, p.n_q_heads, p.q_len, p.head_dim = Q.shape
+    p.n_kv_heads = K.shape[1]
+    if page_table is not None:
+        assert page_table.dtype == torch.int32 and page_table.is_contiguous() and page_table.dim() == 2
+        p.page_table = page_table.data_ptr()
+        p.page_size = K.shape[2]
+        p.max_pages = page_table.shape[1]
+        p.max_kv_len = int(max_kv_len) if max_kv_len is not None else p.max_pages * p.page_size
+    else:
+        p.max_kv_len = K.shape[2] if max_kv_len is None else int(max_kv_len)
+    if kv_lens is not None:
+        assert kv_lens.dtype == torch.int32 and kv_lens.is_contiguous() and kv_lens.shape == (p.batch,)
+        p.kv_lens = kv_lens.data_ptr()
+    p.k, p.bq, p.bk = k, bq, bk
+    p.dtype = _dtype_code(Q)
+    p.flags = flags
+    p.sm_scale = sm_scale
+    p.q_strides = (ctypes.c_int64 * 3)(*Q.stride()[:3])
+    p.kv_strides = (ctypes.c_int64 * 3)(*K.stride()[:3])
+    if O is not None:
+        p.o_strides = (ctypes.c_int64 * 3)(*O.stride()[:3])
+    return p
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,
+                      flags: int = 0, indices: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int32 indices [B, Hq, ceil(Tq/bq), k/bk] of the selected key blocks (see include/hipattn.h)."""
+    _need_gpu(Q, K, kv_lens, page_table, indices)
+    lib = load()
+    p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
+    nqb = (p.q_len + bq - 1) // bq
+    if indices is None:
+        indices = torch.empty((p.batch, p.n_q_heads, nqb, k // bk), dtype=torch.int32, device=Q.device)
+    assert indices.dtype == torch.int32 and indices.is_contiguous()
+    assert indices.numel() == p.batch * p.n_q_heads * nqb * (k // bk)
+    rc = lib.hip_mask_estimate(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), indices.data_ptr(), _stream(Q))
+    if rc != 0:
+        raise HipAttnError(rc)
+    return indices
+
+
+def hip_sparse_attn(Q, K, V, indices, k: int, bq: int, bk: int, kv_lens=None, page_table=None,
+                    max_kv_len=None, sm_scale: float = 0.0, flags: int = 0,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """O [B, Hq, Tq, d]: attention of every query row over its block's selected keys."""
+    _need_gpu(Q, K, V, indices, kv_lens, page_table, out)
+    lib = load()
+    assert V.shape == K.shape and V.stride() == K.stride() and V.dtype == K.dtype == Q.dtype
+    if out is None:
+        out = torch.empty_like(Q)
+    assert out.shape == Q.shape and out.dtype == Q.dtype and out.stride(3) == 1
+    assert indices.dtype == torch.int32 and indices.is_contiguous()
+    p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, sm_scale, flags, O=out)
+    rc = lib.hip_sparse_attn(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), indices.data_ptr(),
+                             out.data_ptr(), _stream(Q))
+    if rc != 0:
+        raise HipAttnError(rc)
+    return out

@@ -1,0 +1,114 @@
+// C ABI of the HiP attention library: argument validation and kernel dispatch.
+#include "../../include/hipattn.h"
+#include "common.h"
+#include "launch.h"
+
+using namespace hipattn;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates the problem and fills the kernel-side view.  Returns HIP_ATTN_OK or an error.
+int prepare(const hip_problem *hp, KParams &kp)
+{
+    if (!hp) return HIP_ATTN_ENULL;
+    const hip_problem &p = *hp;
+    if (p.batch < 0 || p.n_q_heads <= 0 || p.n_kv_heads <= 0 || p.q_len < 0 || p.max_kv_len < 0) return HIP_ATTN_ESHAPE;
+    if (p.n_q_heads % p.n_kv_heads) return HIP_ATTN_ESHAPE;
+    if (p.q_len > p.max_kv_len) return HIP_ATTN_ESHAPE;
+    if (p.head_dim != 64 && p.head_dim != 128) return HIP_ATTN_EHEADDIM;
+    if (p.dtype != HIP_ATTN_F32 && p.dtype != HIP_ATTN_BF16) return HIP_ATTN_EDTYPE;
+    if (p.k <= 0 || p.bk <= 0 || p.bq <= 0 || p.k % p.bk) return HIP_ATTN_EBLOCK;
+    if (p.bq > HIP_ATTN_MAX_BQ || p.bk > HIP_ATTN_MAX_BK) return HIP_ATTN_EBLOCK;
+    if (p.q_len == 1 && p.bq != 1) return HIP_ATTN_EBLOCK;
+    if (p.k / p.bk > HIP_ATTN_MAX_KB) return HIP_ATTN_ETOOLARGE;
+    if (p.page_table && (p.page_size <= 0 || p.page_size % p.bk || p.max_pages <= 0)) return HIP_ATTN_EPAGE;
+    if (p.page_table && (int64_t)p.max_pages * p.page_size < p.max_kv_len) return HIP_ATTN_EPAGE;
+
+    const int d = p.head_dim;
+    const int nqb = (p.q_len + p.bq - 1) / p.bq;
+    if ((int64_t)p.batch * p.n_q_heads * nqb > 0x7fffffffLL) return HIP_ATTN_ETOOLARGE;
+    kp = KParams{};
+    kp.batch = p.batch; kp.hq = p.n_q_heads; kp.hkv = p.n_kv_heads; kp.g = p.n_q_heads / p.n_kv_heads;
+    kp.d = d; kp.q_len = p.q_len; kp.max_kv_len = p.max_kv_len;
+    kp.kb = p.k / p.bk; kp.bq = p.bq; kp.bk = p.bk; kp.nqb = nqb;
+    kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
+    kp.page_size = p.page_size; kp.max_pages = p.max_pages;
+    kp.sm_scale = p.sm_scale > 0.f ? p.sm_scale : 1.0f / sqrtf((float)d);
+
+    auto all_zero = [](const int64_t s[3]) { return s[0] == 0 && s[1] == 0 && s[2] == 0; };
+    if (all_zero(p.q_strides)) { kp.qs_r = d; kp.qs_h = (int64_t)p.q_len * d; kp.qs_b = kp.qs_h * p.n_q_heads; }
+    else { kp.qs_b = p.q_strides[0]; kp.qs_h = p.q_strides[1]; kp.qs_r = p.q_strides[2]; }
+    if (all_zero(p.o_strides)) { kp.os_r = d; kp.os_h = (int64_t)p.q_len * d; kp.os_b = kp.os_h * p.n_q_heads; }
+    else { kp.os_b = p.o_strides[0]; kp.os_h = p.o_strides[1]; kp.os_r = p.o_strides[2]; }
+    if (all_zero(p.kv_strides)) {
+        const int64_t rows = p.page_table ? p.page_size : p.max_kv_len;
+        kp.ks_r = d; kp.ks_h = rows * d; kp.ks_b = kp.ks_h * p.n_kv_heads;
+    } else { kp.ks_b = p.kv_strides[0]; kp.ks_h = p.kv_strides[1]; kp.ks_r = p.kv_strides[2]; }
+
+    // rows must stay 16-byte aligned for the 128-bit loads of the tuned kernels
+    const int64_t per16 = p.dtype == HIP_ATTN_BF16 ? 8 : 4;
+    const int64_t strides[] = {kp.qs_b, kp.qs_h, kp.qs_r, kp.ks_b, kp.ks_h, kp.ks_r, kp.os_b, kp.os_h, kp.os_r};
+    for (int64_t s : strides)
+        if (s < 0 || s % per16) return HIP_ATTN_EALIGN;
+    if (kp.qs_r < d || kp.ks_r < d || kp.os_r < d) return HIP_ATTN_ESHAPE;
+    return HIP_ATTN_OK;
+}
+
+int launch_result(hipError_t e) { return e == hipSuccess ? HIP_ATTN_OK : HIP_ATTN_ELAUNCH - (int)e; }
+
+}  // namespace
+
+extern "C" {
+
+int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream)
+{
+    KParams kp;
+    int rc = prepare(p, kp);
+    if (rc != HIP_ATTN_OK) return rc;
+    if (kp.batch == 0 || kp.q_len == 0) return HIP_ATTN_OK;  // no work units: nothing is read or written
+    if (!Q || !K || !indices) return HIP_ATTN_ENULL;
+    if (!aligned16(Q) || !aligned16(K)) return HIP_ATTN_EALIGN;
+    kp.Q = Q; kp.K = K; kp.idx_out = indices;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf16 = p->dtype == HIP_ATTN_BF16;
+    return launch_result(launch_mask_generic(kp, bf16, st));
+}
+
+int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const void *V, const int32_t *indices,
+                    void *O, void *stream)
+{
+    KParams kp;
+    int rc = prepare(p, kp);
+    if (rc != HIP_ATTN_OK) return rc;
+    if (kp.batch == 0 || kp.q_len == 0) return HIP_ATTN_OK;
+    if (!Q || !K || !V || !indices || !O) return HIP_ATTN_ENULL;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return HIP_ATTN_EALIGN;
+    kp.Q = Q; kp.K = K; kp.V = V; kp.O = O; kp.idx_in = indices;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf16 = p->dtype == HIP_ATTN_BF16;
+    return launch_result(launch_attn_generic(kp, bf16, st));
+}
+
+size_t hip_workspace_bytes(const hip_problem *) { return 0; }
+
+const char *hip_strerror(int code)
+{
+    switch (code) {
+        case HIP_ATTN_OK: return "ok";
+        case HIP_ATTN_ENULL: return "a required pointer is NULL";
+        case HIP_ATTN_ESHAPE: return "invalid shape (sizes, head grouping, q_len > kv_len or row stride < head_dim)";
+        case HIP_ATTN_EBLOCK: return "invalid k / bq / bk (k % bk != 0, block size out of range, or decode with bq != 1)";
+        case HIP_ATTN_EHEADDIM: return "head_dim must be 64 or 128";
+        case HIP_ATTN_EDTYPE: return "dtype must be HIP_ATTN_F32 or HIP_ATTN_BF16";
+        case HIP_ATTN_ETOOLARGE: return "k/bk or the number of work units exceeds the compiled maximum";
+        case HIP_ATTN_EALIGN: return "pointer or stride not 16-byte aligned";
+        case HIP_ATTN_EPAGE: return "invalid page table description";
+        default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
+    }
+}
+
+int hip_attn_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,10 @@
+// Host-side launchers of the kernel families (one translation unit each).
+#pragma once
+#include "common.h"
+
+namespace hipattn {
+
+hipError_t launch_mask_generic(const KParams &p, bool bf16, hipStream_t st);
+hipError_t launch_attn_generic(const KParams &p, bool bf16, hipStream_t st);
+
+}  // namespace hipattn

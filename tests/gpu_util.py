@@ -1,0 +1,111 @@
+"""Helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same seeded
+inputs and compare.  Tolerances:
+  indices  bit-exact on integer-valued inputs; >= 99.9 % equal entries on real-valued inputs
+  output   fp32: max |err| <= 1e-4;  bf16: |err| <= 2e-2 * max(1, |ref| / 4)
+"""
+import numpy as np
+import torch
+
+import oracle
+import paper_2406_09827_amd as hipattn
+from paper_2406_09827_amd import synth
+
+
+def oracle_problem(w, x, n_threads=8):
+    lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
+    table = x["page_table"].cpu().numpy() if x["page_table"] is not None else None
+    return oracle.Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
+                          kv_lens=lens, page_table=table, page_size=w.page_size, n_threads=n_threads)
+
+
+def host(x):
+    return {n: x[n].float().cpu().numpy() for n in ("Q", "K", "V")}
+
+
+def _max_len(w, x):
+    # with a page table the bound is what the table can address
+    return None if x["page_table"] is not None else w.kv_len
+
+
+def gpu_mask(w, x, flags=0):
+    return hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+                                     page_table=x["page_table"], max_kv_len=_max_len(w, x), flags=flags)
+
+
+def gpu_attn(w, x, idx, flags=0, sm_scale=0.0):
+    return hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+                                   page_table=x["page_table"], max_kv_len=_max_len(w, x), sm_scale=sm_scale, flags=flags)
+
+
+def check_output(got, ref, dtype):
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref)
+    if dtype == "fp32":
+        assert err.max() <= 1e-4, f"fp32 output max-abs error {err.max():.3e}"
+    else:
+        bound = 2e-2 * np.maximum(1.0, np.abs(ref) / 4.0)
+        worst = (err / bound).max()
+        assert worst <= 1.0, f"bf16 output error {err.max():.3e} exceeds bound (ratio {worst:.2f})"
+    return float(err.max())
+
+
+def agreement(a, b):
+    a, b = np.asarray(a), np.asarray(b)
+    return float((a == b).mean())
+
+
+def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0):
+    """Full comparison of one workload; returns (agreement, max output error)."""
+    exact = w.integer if exact is None else exact
+    x = synth.make_inputs(w, device="cuda", threads=4)
+    idx_gpu = gpu_mask(w, x, flags)
+    out_gpu = gpu_attn(w, x, idx_gpu, flags, sm_scale)
+    torch.cuda.synchronize()
+    p = oracle_problem(w, x)
+    hx = host(x)
+    all_u = oracle.all_units(p)
+    if units is None:
+        units = all_u
+        sel = np.arange(all_u.shape[0])
+    else:
+        units = np.asarray(units, dtype=np.int32).reshape(-1, 3)
+        nqb = p.n_query_blocks
+        sel = (units[:, 0] * p.n_q_heads + units[:, 1]) * nqb + units[:, 2]
+    idx_g = idx_gpu.cpu().numpy().reshape(-1, p.kb)[sel]
+    idx_ref = oracle.mask_estimate_units(p, hx["Q"], hx["K"], units)
+    if exact:
+        bad = np.nonzero((idx_g != idx_ref).any(axis=1))[0]
+        assert bad.size == 0, f"{bad.size} units differ, first {units[bad[0]]}: {idx_g[bad[0]]} vs {idx_ref[bad[0]]}"
+        agr = 1.0
+    else:
+        agr = agreement(idx_g, idx_ref)
+        assert agr >= 0.999, f"mask agreement {agr:.5f} < 0.999"
+    check_indices_valid(w, x, idx_g, units)
+    # attention is compared on the GPU's own indices so that a near-tie in the mask does not
+    # leak into the output comparison
+    o_ref = oracle.sparse_attn_units(p, hx["Q"], hx["K"], hx["V"], units, idx_g, sm_scale)
+    og = out_gpu.float().cpu().numpy()
+    worst = 0.0
+    for u, (b, h, qb) in enumerate(units):
+        r0 = qb * w.bq
+        n = min(w.bq, w.q_len - r0)
+        worst = max(worst, check_output(og[b, h, r0:r0 + n], o_ref[u, :n], w.dtype))
+    return agr, worst
+
+
+def check_indices_valid(w, x, idx, units):
+    """Invariants that hold for every correct result: count, multiples of bk, ascending,
+    causal, sentinel suffix."""
+    lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
+    kb = w.kb
+    for row, (b, h, qb) in zip(idx, units):
+        kv_len = int(lens[b]) if lens is not None else w.kv_len
+        r0 = qb * w.bq
+        n = min(w.bq, w.q_len - r0)
+        L = min(kv_len, kv_len - w.q_len + r0 + n)
+        Tb = -(-L // w.bk) if L > 0 else 0
+        nv = min(kb, Tb)
+        v = row[:nv].astype(np.int64)
+        assert (row[nv:] == hipattn.SENTINEL).all()
+        assert (v % w.bk == 0).all() and (v >= 0).all() and (v < L).all()
+        assert (np.diff(v) > 0).all()

@@ -1,0 +1,74 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2406_09827_amd as hipattn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hipattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hip_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = hipattn.load()
+    names = _declared_symbols()
+    assert set(names) >= {"hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror"}
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.hip_attn_version() >= 100
+
+
+def _ok_problem():
+    p = hipattn.HipProblem()
+    p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim = 1, 4, 2, 128
+    p.q_len, p.max_kv_len, p.k, p.bq, p.bk, p.dtype = 64, 64, 32, 16, 2, hipattn.BF16
+    return p
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "k", 33), -3),
+    (lambda p: setattr(p, "bq", 65), -3),
+    (lambda p: setattr(p, "bk", 0), -3),
+    (lambda p: setattr(p, "head_dim", 96), -4),
+    (lambda p: setattr(p, "dtype", 7), -5),
+    (lambda p: setattr(p, "n_kv_heads", 3), -2),
+    (lambda p: setattr(p, "q_len", 65), -2),
+    (lambda p: (setattr(p, "k", 4096), setattr(p, "bk", 2)), -6),
+    (lambda p: (setattr(p, "q_len", 1), setattr(p, "bq", 16)), -3),
+    (lambda p: (setattr(p, "page_table", 4096), setattr(p, "page_size", 3), setattr(p, "max_pages", 64)), -8),
+    (lambda p: setattr(p, "q_strides", (ctypes.c_int64 * 3)(8192, 130, 2)), -7),
+])
+def test_argument_errors_before_launch(mutate, code):
+    lib = hipattn.load()
+    p = _ok_problem()
+    mutate(p)
+    fake = ctypes.c_void_p(4096)   # never dereferenced: validation fails first
+    assert lib.hip_mask_estimate(ctypes.byref(p), fake, fake, fake, None) == code
+    assert lib.hip_sparse_attn(ctypes.byref(p), fake, fake, fake, fake, fake, None) == code
+    assert lib.hip_strerror(code) not in (None, b"", b"unknown error")
+
+
+def test_null_and_misaligned_pointers():
+    lib = hipattn.load()
+    p = _ok_problem()
+    fake = ctypes.c_void_p(4096)
+    assert lib.hip_mask_estimate(None, fake, fake, fake, None) == -1
+    assert lib.hip_mask_estimate(ctypes.byref(p), None, fake, fake, None) == -1
+    assert lib.hip_sparse_attn(ctypes.byref(p), fake, fake, None, fake, fake, None) == -1
+    assert lib.hip_mask_estimate(ctypes.byref(p), ctypes.c_void_p(4100), fake, fake, None) == -7
+    assert lib.hip_workspace_bytes(ctypes.byref(p)) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    q = torch.zeros(1, 1, 16, 64)
+    with pytest.raises(RuntimeError):
+        hipattn.hip_mask_estimate(q, q, 8, 4, 2)

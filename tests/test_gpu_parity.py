@@ -1,0 +1,100 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_09827_amd import synth, FORCE_GENERIC
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+FLAG_SETS = [pytest.param(FORCE_GENERIC, id="generic"), pytest.param(0, id="tuned")]
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+def test_c1_integer_bit_exact(flags):
+    U.run_case(synth.C1_INT, flags)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+def test_c1_normal(flags):
+    agr, err = U.run_case(synth.C1, flags)
+    print(f"c1 agreement {agr:.6f} max err {err:.3e}")
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_c2_shape_reduced(flags, integer):
+    # C2's head layout, block sizes and k, at T = 4096 + a ragged tail (several tiles, short last block)
+    w = synth.scaled(synth.C2, q_len=4096 + 40, kv_len=4096 + 40, n_q_heads=8, n_kv_heads=2, spike_every=1024,
+                     integer=integer)
+    rng = np.random.default_rng(0)
+    nqb = w.n_query_blocks
+    qbs = sorted(set([0, 7, 8, 9, 15, 16, 17, 31, 32, 33, 64, nqb - 2, nqb - 1] + rng.integers(0, nqb, 12).tolist()))
+    units = [(0, h, qb) for h in range(w.n_q_heads) for qb in qbs]
+    agr, err = U.run_case(w, flags, units=units)
+    print(f"c2-reduced agreement {agr:.6f} max err {err:.3e}")
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_c4_shape_reduced(flags, integer):
+    w = synth.scaled(synth.C4, q_len=8192 + 70, kv_len=8192 + 70, n_q_heads=4, n_kv_heads=2, integer=integer)
+    nqb = w.n_query_blocks
+    units = [(0, h, qb) for h in range(w.n_q_heads) for qb in (0, 15, 16, 17, 40, 64, 65, nqb - 2, nqb - 1)]
+    U.run_case(w, flags, units=units)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_decode_contiguous(flags, integer):
+    w = synth.scaled(synth.C3, batch=3, kv_len=20000, integer=integer)
+    U.run_case(w, flags)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_decode_ragged_paged(flags, integer):
+    w = synth.scaled(synth.C5, batch=6, kv_len=9000, ragged=(700, 9000), integer=integer)
+    U.run_case(w, flags)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("T,k,bq,bk,d,hq,hkv,dtype", [
+    (1, 8, 1, 1, 64, 1, 1, "fp32"),        # a single token
+    (37, 64, 4, 2, 64, 2, 1, "fp32"),      # k >= T: everything visible is selected (dense)
+    (130, 12, 8, 4, 128, 2, 2, "bf16"),    # kb = 3, not a power of two; T % bk != 0; short last block
+    (257, 10, 1, 1, 64, 1, 1, "bf16"),     # token-level search (bq = bk = 1), kb = 10
+    (300, 64, 64, 16, 128, 4, 1, "fp32"),  # largest blocks
+    (1500, 2048, 16, 2, 64, 1, 1, "bf16"), # kb = 1024 (the maximum), mostly dense
+    (5000, 2048, 16, 2, 64, 1, 1, "fp32"), # kb = 1024 with pruning
+])
+def test_edge_shapes(flags, T, k, bq, bk, d, hq, hkv, dtype):
+    for integer in (True, False):
+        w = synth.Workload("edge", 2, hq, hkv, d, T, T, k, bq, bk, dtype, rho=0.9, integer=integer, seed=77)
+        units = None
+        if T >= 1500:
+            nqb = w.n_query_blocks
+            units = [(b, 0, qb) for b in range(2) for qb in (0, nqb // 2, nqb - 1)]
+        U.run_case(w, flags, units=units)
+
+
+def test_empty_batch_and_strided_views():
+    import paper_2406_09827_amd as hipattn
+    w = synth.scaled(synth.C1, integer=True, n_q_heads=2)
+    x = synth.make_inputs(w, device="cuda", threads=1)
+    # zero sequences: nothing is launched, nothing is written
+    q0 = x["Q"][:0]
+    idx0 = hipattn.hip_mask_estimate(q0, x["K"][:0], w.k, w.bq, w.bk)
+    assert idx0.numel() == 0
+    # token-major storage [B, T, H, d] viewed as [B, H, T, d]: strides go through the ABI
+    Qt = x["Q"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Kt = x["K"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    Vt = x["V"].permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not Qt.is_contiguous()
+    a = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk)
+    bidx = hipattn.hip_mask_estimate(Qt, Kt, w.k, w.bq, w.bk)
+    assert torch.equal(a, bidx)
+    oa = hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], a, w.k, w.bq, w.bk)
+    ob = hipattn.hip_sparse_attn(Qt, Kt, Vt, a, w.k, w.bq, w.bk, out=torch.empty_like(Qt))
+    assert torch.equal(oa, ob)
