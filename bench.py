@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the HiP hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is already
+resident in HBM: hip_mask_estimate followed by hip_sparse_attn for one attention layer.
+Prints ONE JSON line (see DESIGN.md "Measurement" for every field).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def rounds_of(Tb: int, kb: int) -> int:
+    """Rounds a query block with Tb visible key blocks needs: ceil(log2(ceil(Tb/kb)))."""
+    if Tb <= kb:
+        return 0
+    c = -(-Tb // kb)
+    return (c - 1).bit_length()
+
+
+def mask_algorithmic_bytes(w, kv_lens) -> float:
+    """Key bytes the method has to touch in mask estimation, counted conservatively:
+    every round but a unit's last scores 2*kb branches, the last at least kb (nodes that are
+    already one block long have a single branch); plus the query block once and the indices."""
+    size = 2 if w.dtype == "bf16" else 4
+    row = w.head_dim * size
+    total = 0.0
+    for b in range(w.batch):
+        kv_len = int(kv_lens[b]) if kv_lens is not None else w.kv_len
+        for qb in range(w.n_query_blocks):
+            r0 = qb * w.bq
+            n = min(w.bq, w.q_len - r0)
+            L = min(kv_len, kv_len - w.q_len + r0 + n)
+            Tb = -(-L // w.bk) if L > 0 else 0
+            R = rounds_of(Tb, w.kb)
+            branches = (R - 1) * 2 * w.kb + w.kb if R > 0 else 0
+            total += branches * w.bk * row + n * row + w.kb * 4
+    return total * w.n_q_heads
+
+
+def attn_algorithmic(w, kv_lens):
+    """(flops, bytes) of the sparse attention: 4*rows*keys*d flops per unit over the selected
+    keys that exist (k, or the visible prefix when shorter); K and V rows gathered once per unit."""
+    size = 2 if w.dtype == "bf16" else 4
+    flops = 0.0
+    byts = 0.0
+    for b in range(w.batch):
+        kv_len = int(kv_lens[b]) if kv_lens is not None else w.kv_len
+        for qb in range(w.n_query_blocks):
+            r0 = qb * w.bq
+            n = min(w.bq, w.q_len - r0)
+            L = min(kv_len, kv_len - w.q_len + r0 + n)
+            keys = min(w.k, max(L, 0))
+            flops += 4.0 * n * keys * w.head_dim
+            byts += 2.0 * keys * w.head_dim * size + 2.0 * n * w.head_dim * size
+    return flops * w.n_q_heads, byts * w.n_q_heads
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), kept as
+    a small text file under profiles/ (key = value lines); None when no such file exists."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{name}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        line = line.split("#")[0]
+        if "=" in line:
+            k, v = line.split("=", 1)
+            vals[k.strip()] = v.strip()
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(w, x, budget_s: float):
+    """The CPU oracle timed on a bounded random sample of (head, query block) units of the same
+    workload (mask estimation + sparse attention), all host cores via OpenMP."""
+    import numpy as np
+    import oracle
+    from tests.gpu_util import oracle_problem, host
+
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 10**6))
+    p = oracle_problem(w, x, n_threads=cores)
+    hx = host(x)
+    rng = np.random.default_rng(1234)
+    all_u = oracle.all_units(p)
+
+    def run(n):
+        sel = rng.choice(all_u.shape[0], size=min(n, all_u.shape[0]), replace=False)
+        units = all_u[sel]
+        t0 = time.perf_counter()
+        idx = oracle.mask_estimate_units(p, hx["Q"], hx["K"], units)
+        oracle.sparse_attn_units(p, hx["Q"], hx["K"], hx["V"], units, idx)
+        return time.perf_counter() - t0, units.shape[0]
+
+    t_pilot, n_pilot = run(4 * cores)
+    n = int(max(4 * cores, min(all_u.shape[0], n_pilot * budget_s / max(t_pilot, 1e-3))))
+    t, n = run(n)
+    rows = n * w.bq / w.n_q_heads          # layer-tokens covered by the sample
+    if w.q_len == 1:
+        value, unit = t / (n / (w.batch * w.n_q_heads)) * 1e6, "us/step"
+    else:
+        value, unit = rows / t, "tokens/s"
+    return {"value": value, "unit": unit, "cores": cores, "kind": "oracle",
+            "sample": f"{n} random (sequence, head, query block) units of {all_u.shape[0]}, "
+                      f"{t:.1f} s wall, extrapolated linearly"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 disables")
+    ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2406_09827_amd as hipattn
+    from paper_2406_09827_amd import synth
+
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    flags = hipattn.FORCE_GENERIC if args.generic else 0
+    t0 = time.perf_counter()
+    x = synth.make_inputs(w, device="cuda", threads=16)
+    torch.cuda.synchronize()
+    print(f"[bench] {w.name}: inputs ready in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    kv_lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
+    max_len = None if x["page_table"] is not None else w.kv_len
+    idx = torch.empty((w.batch, w.n_q_heads, w.n_query_blocks, w.kb), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(x["Q"])
+
+    def step():
+        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                  max_kv_len=max_len, flags=flags, indices=idx)
+        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out)
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # events are recorded on torch's current stream, the stream the kernels are launched on
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                  max_kv_len=max_len, flags=flags, indices=idx)
+        ev[i][1].record()
+        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ms_mask = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    ms_attn = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+
+    mask_bytes = mask_algorithmic_bytes(w, kv_lens)
+    attn_flops, attn_bytes = attn_algorithmic(w, kv_lens)
+    mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
+    attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
+    attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
+    if ms_mask >= ms_attn:
+        roof = {"kernel": "mask_estimate", "bound": "hbm", "achieved": mask_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{args.workload}")}
+    elif w.q_len == 1:
+        roof = {"kernel": "sparse_attn", "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": attn_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"sparse_attn_{args.workload}")}
+    else:
+        roof = {"kernel": "sparse_attn", "bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": read_traffic(f"sparse_attn_{args.workload}")}
+
+    if w.q_len == 1:
+        metric, unit, value, hib = f"HiP decode us/step @{w.kv_len // 1024}k ctx", "us/step", ms_step * 1e3, False
+    else:
+        metric, unit, value, hib = (f"HiP prefill tokens/s @T={w.kv_len // 1024}k", "tokens/s",
+                                    w.batch * w.q_len / (ms_step * 1e-3), True)
+    res = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": hib, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
+                   "kernels": "generic" if args.generic else "tuned"},
+        "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
+        "mask_estimate": {"algorithmic_GB": mask_bytes / 1e9, "GB/s": mask_gbs, "frac_hbm_peak": mask_gbs / HBM_PEAK_GBS},
+        "sparse_attn": {"algorithmic_TFLOP": attn_flops / 1e12, "TFLOP/s": attn_tflops,
+                        "frac_mfma_bf16_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                        "gathered_GB": attn_bytes / 1e9, "GB/s": attn_gbs},
+        "roofline": roof,
+    }
+    if args.cpu_budget > 0:
+        res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
