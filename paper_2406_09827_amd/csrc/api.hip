@@ -73,6 +73,8 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     kp.Q = Q; kp.K = K; kp.idx_out = indices;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
+    const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
+    if (!generic && mask_mfma_supported(kp, bf16)) return launch_result(launch_mask_mfma(kp, st));
     return launch_result(launch_mask_generic(kp, bf16, st));
 }
 
