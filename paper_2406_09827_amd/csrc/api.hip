@@ -90,6 +90,8 @@ int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const vo
     kp.Q = Q; kp.K = K; kp.V = V; kp.O = O; kp.idx_in = indices;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
+    const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
+    if (!generic && attn_mfma_supported(kp, bf16)) return launch_result(launch_attn_mfma(kp, st));
     return launch_result(launch_attn_generic(kp, bf16, st));
 }
 

@@ -1,0 +1,280 @@
+// Block-sparse attention for bf16 prefill on CDNA4 matrix cores (paper Eq. 2-3; the
+// "block sparse flash attention" of the appendix: online softmax over the gathered keys).
+//
+// Work item = one wave = one (sequence, query head, query block, 32-row query tile); four
+// independent work items per workgroup, no workgroup barrier anywhere.
+// Per tile of 32 gathered keys:
+//   S^T = K_tile . Q^T     v_mfma_f32_32x32x16_bf16, A = key rows loaded straight from global
+//                          memory (lane = key row), B = the query tile held in registers.
+//                          The result has one query per lane and 16 keys in its registers,
+//                          so the softmax statistics of a query are lane-local (plus one
+//                          exchange with lane ^ 32) and P^T is already in B-operand layout.
+//   O^T += V_tile^T . P^T  (P as hi + lo bf16 terms) the value rows are loaded coalesced, staged in this wave's LDS
+//                          slice and read back channel-major (the contraction runs over
+//                          keys, so V has to be transposed on the way to the A operand).
+// The key positions of a tile and their row offsets are published through a small per-wave
+// LDS array so that every lane can mask by (key position, query position).
+#include "common.h"
+#include "launch.h"
+
+namespace hipattn {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
+{
+    constexpr int KS = D / 16;     // k-steps of S^T = K Q^T
+    constexpr int CT = D / 32;     // 32-channel tiles of O^T
+    constexpr int PITCH = D + 8;   // LDS row pitch in bf16: 16 bytes of padding per row
+    constexpr int CPR = D / 8;     // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;  // rows covered by one wave-wide 16-byte load
+    constexpr int NLD = 32 / RPI;  // such loads per 32-row tile
+    __shared__ __attribute__((aligned(16))) bf16_t vt_s[4][32 * PITCH];
+    __shared__ __attribute__((aligned(16))) int tk_s[4][32];
+    __shared__ __attribute__((aligned(16))) int64_t vo_s[4][32];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, hh = lane >> 5;
+
+    // ---- which (sequence, head, query block, query tile) this wave owns
+    const int64_t groups = (int64_t)p.batch * p.hkv;
+    const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
+    int64_t group, o;
+    if (xcd_map) {  // blockIdx.x % 8 = XCD: all work of a KV head goes to one XCD's L2
+        const int64_t bid = blockIdx.x;
+        const int64_t seq = (bid >> 3) * 4 + wave;
+        group = (bid & 7) + 8 * (seq / per_group);
+        o = seq % per_group;
+    } else {
+        const int64_t lin = (int64_t)blockIdx.x * 4 + wave;
+        group = lin / per_group;
+        o = lin % per_group;
+    }
+    if (group >= groups) return;
+    const int qb = p.nqb - 1 - (int)(o / (p.g * mtn));
+    const int rem = (int)(o % (p.g * mtn));
+    const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
+    const int h = hk * p.g + rem / mtn, mt = rem % mtn;
+
+    const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
+    const int row0 = qb * p.bq + mt * 32;
+    const int n_rows = min(32, min(p.bq, p.q_len - qb * p.bq) - mt * 32);
+    if (n_rows <= 0) return;
+    const int pos0 = kv_len - p.q_len + row0;  // position of this tile's first query row
+    const int32_t *idx = p.idx_in + (((int64_t)b * p.hq + h) * p.nqb + qb) * p.kb;
+    const int bk = 1 << log_bk;
+    const int n_keys = p.kb << log_bk, n_tiles = (n_keys + 31) >> 5;
+
+    // ---- query tile as B operand (lane: query col, channels kk*16 + hh*8 ..)
+    bf16x8 qf[KS];
+    {
+        const bf16_t *Qb = (const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + (int64_t)row0 * p.qs_r;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (col < n_rows) v = *(const uint4 *)(Qb + (int64_t)col * p.qs_r + kk * 16 + hh * 8);
+            qf[kk] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    const bf16_t *Kbase = (const bf16_t *)p.K, *Vbase = (const bf16_t *)p.V;
+    bf16_t *vt = vt_s[wave];
+    int *tk = tk_s[wave];
+    int64_t *vo = vo_s[wave];
+
+    const float c = p.sm_scale * 1.44269504088896340736f;  // scores are kept in log2 units
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 oacc[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[ct][r] = 0.f;
+
+    // key row `col` of a tile: logical position (or -1), row offset, and its K data
+    uint4 kr[KS];
+    int t_c;
+    int64_t off_c;
+    auto fetch_k = [&](int tile) {
+        const int ki = tile * 32 + col;
+        t_c = -1;
+        off_c = 0;
+        if (ki < n_keys) {
+            const int first = idx[ki >> log_bk];
+            const int t = first + (ki & (bk - 1));
+            if (first >= 0 && first < kv_len && t < kv_len) t_c = t;
+        }
+        if (t_c >= 0) {
+            off_c = kv_row_offset(p, b, hk, t_c);
+            const bf16_t *src = Kbase + off_c + hh * 8;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) kr[kk] = *(const uint4 *)(src + kk * 16);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) kr[kk] = make_uint4(0, 0, 0, 0);
+        }
+    };
+
+    fetch_k(0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const bool any_valid = __ballot(t_c >= 0 && t_c <= pos0 + n_rows - 1) != 0;
+        if (hh == 0) { tk[col] = t_c; vo[col] = off_c; }
+        wave_lds_sync();
+
+        uint4 vr[NLD];
+        f32x16 sacc;
+        if (any_valid) {
+            // value rows of this tile, coalesced: 16-byte chunk (lane % CPR) of row lane / CPR + i*RPI
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int row = lane / CPR + i * RPI;
+                vr[i] = make_uint4(0, 0, 0, 0);
+                if (tk[row] >= 0) vr[i] = *(const uint4 *)(Vbase + vo[row] + (lane % CPR) * 8);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kr[kk]), qf[kk], sacc, 0, 0, 0);
+        }
+        // positions of the 16 keys this lane holds scores for: rows 8g + 4hh + {0..3}
+        int4 tq[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) tq[g] = *(const int4 *)(tk + 8 * g + 4 * hh);
+        wave_lds_sync();  // tk/vo are consumed; the next fetch may overwrite nothing yet, but keep order
+
+        if (tile + 1 < n_tiles) fetch_k(tile + 1);  // next keys in flight during softmax and P.V
+        if (!any_valid) continue;
+
+        // ---- online softmax for query `col` (both half-waves hold the same query)
+        const int qpos = pos0 + col;
+        float s[16], mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int g = r >> 2;
+            const int tkey = (r & 3) == 0 ? tq[g].x : (r & 3) == 1 ? tq[g].y : (r & 3) == 2 ? tq[g].z : tq[g].w;
+            const bool ok = tkey >= 0 && tkey <= qpos;
+            s[r] = ok ? sacc[r] * c : -INFINITY;
+            mx = fmaxf(mx, s[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        float lsum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s[r] = __builtin_amdgcn_exp2f(s[r] - m_safe);
+            lsum += s[r];
+        }
+        l_run = l_run * alpha + lsum;
+        m_run = m_new;
+        if (__ballot(alpha != 1.f) != 0) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[ct][r] *= alpha;
+        }
+        // P^T as B operand of the two 16-key steps (registers 8*st .. 8*st+7), carried as a
+        // two-term bf16 expansion p = hi + lo so that rounding P does not limit the output
+        bf16x8 pb[2], pl[2];
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                const float a0 = s[8 * st + 2 * e2], a1 = s[8 * st + 2 * e2 + 1];
+                hi[e2] = pack_bf16(a0, a1);
+                lo[e2] = pack_bf16(a0 - __uint_as_float(hi[e2] << 16), a1 - __uint_as_float(hi[e2] & 0xffff0000u));
+            }
+            pb[st] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            pl[st] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+        }
+
+        // ---- stage V in LDS, read it back channel-major, O^T += V^T P^T
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+            const int row = lane / CPR + i * RPI;
+            *(uint4 *)(vt + row * PITCH + (lane % CPR) * 8) = vr[i];
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                // A operand: channel ct*32 + col, keys (2st + e/4)*8 + 4hh + e%4, e = 0..7
+                const bf16_t *src = vt + ((2 * st) * 8 + 4 * hh) * PITCH + ct * 32 + col;
+                uint32_t w[4];
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int k0 = ((2 * e2) >> 2) * 8 + ((2 * e2) & 3);
+                    w[e2] = (uint32_t)src[k0 * PITCH] | ((uint32_t)src[(k0 + 1) * PITCH] << 16);
+                }
+                uint4 u = make_uint4(w[0], w[1], w[2], w[3]);
+                const bf16x8 va = __builtin_bit_cast(bf16x8, u);
+                oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
+                oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
+            }
+        }
+        wave_lds_sync();
+    }
+
+    // ---- normalise, transpose through LDS, coalesced store
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint2 u;
+            u.x = pack_bf16(oacc[ct][4 * g + 0] * inv, oacc[ct][4 * g + 1] * inv);
+            u.y = pack_bf16(oacc[ct][4 * g + 2] * inv, oacc[ct][4 * g + 3] * inv);
+            *(uint2 *)(vt + col * PITCH + ct * 32 + g * 8 + hh * 4) = u;
+        }
+    wave_lds_sync();
+    bf16_t *Ob = (bf16_t *)p.O + (int64_t)b * p.os_b + (int64_t)h * p.os_h + (int64_t)row0 * p.os_r;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int row = lane / CPR + i * RPI;
+        if (row < n_rows) *(uint4 *)(Ob + (int64_t)row * p.os_r + (lane % CPR) * 8) = *(const uint4 *)(vt + row * PITCH + (lane % CPR) * 8);
+    }
+}
+
+bool attn_mfma_supported(const KParams &p, bool bf16)
+{
+    return bf16 && p.q_len > 1 && p.bk <= 16 && (p.bk & (p.bk - 1)) == 0 && p.bq <= 64;
+}
+
+hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
+{
+    int log_bk = 0;
+    while ((1 << log_bk) < p.bk) ++log_bk;
+    const int mtn = (p.bq + 31) / 32;
+    const int64_t groups = (int64_t)p.batch * p.hkv;
+    const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
+    const int xcd_map = (groups % 8 == 0 && per_group % 4 == 0) ? 1 : 0;
+    const int64_t waves = groups * per_group;
+    if (waves == 0) return hipSuccess;
+    dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
+    if (p.d == 64) hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+    else hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+    return hipGetLastError();
+}
+
+}  // namespace hipattn
