@@ -75,6 +75,7 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
     if (!generic && mask_mfma_supported(kp, bf16)) return launch_result(launch_mask_mfma(kp, st));
+    if (!generic && mask_decode_supported(kp, bf16)) return launch_result(launch_mask_decode(kp, st));
     return launch_result(launch_mask_generic(kp, bf16, st));
 }
 
@@ -92,6 +93,7 @@ int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const vo
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
     if (!generic && attn_mfma_supported(kp, bf16)) return launch_result(launch_attn_mfma(kp, st));
+    if (!generic && attn_decode_supported(kp, bf16)) return launch_result(launch_attn_decode(kp, st));
     return launch_result(launch_attn_generic(kp, bf16, st));
 }
 

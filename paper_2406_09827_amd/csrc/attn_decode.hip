@@ -1,0 +1,138 @@
+// Block-sparse attention for single-query decode in bf16 (paper Eq. 2-3 for one query row
+// per sequence; the sparse-attention step of Alg. 2).
+//
+// One wave per (sequence, query head).  A key row is read by D/8 lanes (16 bytes each),
+// so a wave-wide load covers 64/(D/8) rows; each such lane group walks its own subset of the
+// selected blocks with its own online-softmax state (running max, sum and 8 output channels
+// per lane), loading the value row of a key right next to its key row.  The groups'
+// states are merged at the end with a few cross-lane exchanges.  Everything is fp32 after
+// the loads; HBM bound (K and V rows are touched exactly once).
+#include "common.h"
+#include "launch.h"
+
+namespace hipattn {
+
+template <int BK, int D>
+__global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
+{
+    constexpr int LPR = D / 8, RPW = 64 / LPR;
+    constexpr int U = BK >= 4 ? 1 : 4 / BK;  // blocks in flight per lane group (4 key + 4 value rows)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane / LPR, lc = lane % LPR;
+    const int64_t wg = (int64_t)blockIdx.x * 4 + wave;
+    if (wg >= (int64_t)p.batch * p.hq) return;
+    const int b = (int)(wg / p.hq), h = (int)(wg % p.hq), hk = h / p.g;
+    const int kb = p.kb;
+    const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
+    const int32_t *idx = p.idx_in + wg * kb;
+
+    const uint4 qv = *(const uint4 *)((const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + lc * 8);
+    const bf16_t *Kbase = (const bf16_t *)p.K, *Vbase = (const bf16_t *)p.V;
+    const float c = p.sm_scale * 1.44269504088896340736f;
+
+    float m_run = -INFINITY, l_run = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+    for (int base = 0; base < kb; base += RPW * U) {
+        uint4 kr[U][BK], vr[U][BK];
+        bool ok[U][BK];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = base + u * RPW + grp;
+            int first = -1;
+            if (j < kb) first = idx[j];
+            const bool blk = first >= 0 && first < kv_len;
+            int64_t off = 0;
+            if (blk) off = kv_row_offset(p, b, hk, first) + lc * 8;
+#pragma unroll
+            for (int n = 0; n < BK; ++n) {
+                ok[u][n] = blk && first + n < kv_len;  // the query is the last position: no key is in its future
+                kr[u][n] = make_uint4(0, 0, 0, 0);
+                vr[u][n] = make_uint4(0, 0, 0, 0);
+                if (ok[u][n]) {
+                    kr[u][n] = *(const uint4 *)(Kbase + off + (int64_t)n * p.ks_r);
+                    vr[u][n] = *(const uint4 *)(Vbase + off + (int64_t)n * p.ks_r);
+                }
+            }
+        }
+        float s[U][BK], mx = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int n = 0; n < BK; ++n) {
+                const float d = row_group_sum<LPR>(dot8_bf16(qv, kr[u][n])) * c;
+                s[u][n] = ok[u][n] ? d : -INFINITY;
+                mx = fmaxf(mx, s[u][n]);
+            }
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        l_run *= alpha;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= alpha;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int n = 0; n < BK; ++n) {
+                const float pr = __builtin_amdgcn_exp2f(s[u][n] - m_safe);
+                l_run += pr;
+                const uint32_t w[4] = {vr[u][n].x, vr[u][n].y, vr[u][n].z, vr[u][n].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] = fmaf(pr, __uint_as_float(w[i] << 16), acc[2 * i]);
+                    acc[2 * i + 1] = fmaf(pr, __uint_as_float(w[i] & 0xffff0000u), acc[2 * i + 1]);
+                }
+            }
+        m_run = m_new;
+    }
+
+    // merge the lane groups' partial softmax states (same channels, different keys)
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        const float m_o = __shfl_xor(m_run, off, 64), l_o = __shfl_xor(l_run, off, 64);
+        const float m_new = fmaxf(m_run, m_o);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float a = __builtin_amdgcn_exp2f(m_run - m_safe), ao = __builtin_amdgcn_exp2f(m_o - m_safe);
+        l_run = l_run * a + l_o * ao;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off, 64) * ao;
+        m_run = m_new;
+    }
+    if (grp == 0) {
+        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+        uint4 o;
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)f32_to_bf16(acc[2 * i] * inv) | ((uint32_t)f32_to_bf16(acc[2 * i + 1] * inv) << 16);
+        o = make_uint4(w[0], w[1], w[2], w[3]);
+        *(uint4 *)((bf16_t *)p.O + (int64_t)b * p.os_b + (int64_t)h * p.os_h + lc * 8) = o;
+    }
+}
+
+bool attn_decode_supported(const KParams &p, bool bf16)
+{
+    return bf16 && p.q_len == 1 && p.bq == 1 && (p.bk == 1 || p.bk == 2 || p.bk == 4);
+}
+
+hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
+{
+    const int64_t waves = (int64_t)p.batch * p.hq;
+    if (waves == 0) return hipSuccess;
+    dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
+#define HIPATTN_LAUNCH(BKV, DV) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV>), grid, block, 0, st, p)
+    if (p.d == 64) {
+        if (p.bk == 1) HIPATTN_LAUNCH(1, 64);
+        else if (p.bk == 2) HIPATTN_LAUNCH(2, 64);
+        else HIPATTN_LAUNCH(4, 64);
+    } else {
+        if (p.bk == 1) HIPATTN_LAUNCH(1, 128);
+        else if (p.bk == 2) HIPATTN_LAUNCH(2, 128);
+        else HIPATTN_LAUNCH(4, 128);
+    }
+#undef HIPATTN_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace hipattn

@@ -118,4 +118,43 @@ __device__ __forceinline__ void select_topk_ordered(const uint32_t (&key)[E], in
     }
 }
 
+// ---- wave-local helpers -----------------------------------------------------------------
+
+// Orders LDS traffic of ONE wave: lanes may read what other lanes of the same wave wrote
+// before this point.  (LDS executes a wave's accesses in order; this only stops the compiler
+// from moving them.)
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the LPR (8 or 16) consecutive lanes that share a key row; every lane gets the sum.
+template <int LPR> __device__ __forceinline__ float row_group_sum(float v)
+{
+    v += dpp_f<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);  // row_half_mirror
+    if (LPR == 16) v += dpp_f<0x140>(v);  // row_mirror
+    return v;
+}
+
+// fp32 dot product of two runs of 8 bf16 values (v_dot2_f32_bf16 x 4).
+__device__ __forceinline__ float dot8_bf16(const uint4 &a, const uint4 &b)
+{
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    float acc = 0.f;
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.z), __builtin_bit_cast(bf16x2_t, b.z), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), acc, false);
+    return acc;
+}
+
 }  // namespace hipattn

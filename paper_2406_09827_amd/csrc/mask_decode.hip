@@ -1,0 +1,155 @@
+// Hierarchical mask estimation for single-query decode in bf16 (paper Alg. 2: one run of
+// Alg. 1 per step over the current context, with bq = 1).
+//
+// With one query row the branch scoring is vector x gathered-rows work: bandwidth bound, no
+// use for the matrix cores.  One WAVE per (sequence, query head); the four waves of a
+// workgroup are the query heads of one KV group when Hq/Hkv = 4, so in the first round,
+// where all heads of a group score the same representative blocks, their loads meet in the
+// L1/L2 instead of going to HBM four times.
+//   * a key row is read by D/8 lanes, 16 bytes each (a full 128-bit coalesced row segment),
+//     multiplied with v_dot2_f32_bf16 and summed over the lanes with DPP adds;
+//   * several blocks per lane group are in flight at once (8 loads per lane);
+//   * scores -> per-wave LDS keys -> ordered threshold selection (once per wave, nothing
+//     redundant) -> the wave's private node list.  No workgroup barrier anywhere.
+// Ragged lengths (kv_lens) and a page table are handled per row.
+#include "common.h"
+#include "launch.h"
+
+namespace hipattn {
+
+template <int E, int BK, int D>
+__global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
+{
+    constexpr int NB = 64 * E;
+    constexpr int LPR = D / 8;        // lanes per key row
+    constexpr int RPW = 64 / LPR;     // rows (= branches) per wave-wide load
+    constexpr int U = BK >= 8 ? 1 : 8 / BK;  // branches in flight per lane group
+    __shared__ uint32_t keys_s[4][NB];
+    __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = lane / LPR, lc = lane % LPR;
+    const int64_t wg = (int64_t)blockIdx.x * 4 + wave;
+    if (wg >= (int64_t)p.batch * p.hq) return;
+    const int b = (int)(wg / p.hq), h = (int)(wg % p.hq), hk = h / p.g;
+    const int kb = p.kb;
+    const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
+    int32_t *out = p.idx_out + wg * kb;
+
+    const int Tb = kv_len > 0 ? (kv_len + BK - 1) / BK : 0;
+    if (Tb <= kb) {
+        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j * BK : kSentinel;
+        return;
+    }
+
+    const uint4 qv = *(const uint4 *)((const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + lc * 8);
+    uint32_t *keys = keys_s[wave];
+    for (int i = lane; i < NB; i += 64) keys[i] = 0;
+    {
+        const int a = Tb / kb, r = Tb % kb;
+        for (int j = lane; j < kb; j += 64) {
+            nds[wave][0][j] = chunk_bound(j, a, r, kb);
+            nde[wave][0][j] = chunk_bound(j + 1, a, r, kb);
+        }
+    }
+    wave_lds_sync();
+
+    const bf16_t *Kbase = (const bf16_t *)p.K;
+    int cur = 0;
+    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
+        const int *ns = nds[wave][cur], *ne = nde[wave][cur];
+
+        for (int base = 0; base < 2 * kb; base += RPW * U) {
+            uint4 kv[U][BK];
+            bool ok[U];
+            int t0[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int slot = base + u * RPW + grp, node = slot >> 1;
+                ok[u] = node < kb;
+                t0[u] = 0;
+                if (ok[u]) {
+                    const int s = ns[node], e = ne[node];
+                    const int mid = s + ((e - s) >> 1);
+                    const int bs = (slot & 1) ? mid : s, be = (slot & 1) ? e : mid;
+                    ok[u] = be > bs;
+                    t0[u] = (bs + ((be - bs) >> 1)) * BK;
+                }
+                const bf16_t *src = nullptr;
+                if (ok[u]) src = Kbase + kv_row_offset(p, b, hk, t0[u]) + lc * 8;
+#pragma unroll
+                for (int n = 0; n < BK; ++n) {
+                    kv[u][n] = make_uint4(0, 0, 0, 0);
+                    if (ok[u] && t0[u] + n < kv_len) kv[u][n] = *(const uint4 *)(src + (int64_t)n * p.ks_r);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float best = -INFINITY;
+#pragma unroll
+                for (int n = 0; n < BK; ++n) {
+                    const float dsum = row_group_sum<LPR>(dot8_bf16(qv, kv[u][n]));
+                    if (t0[u] + n < kv_len) best = fmaxf(best, dsum);
+                }
+                const int slot = base + u * RPW + grp;
+                if (lc == 0 && slot < NB) keys[slot] = ok[u] ? score_key(best) : 0u;
+            }
+        }
+        wave_lds_sync();
+
+        uint32_t key[E];
+        bool keep[E];
+        int dest[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
+        select_topk_ordered<E>(key, kb, keep, dest);
+        int *ns2 = nds[wave][cur ^ 1], *ne2 = nde[wave][cur ^ 1];
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            if (keep[i]) {
+                const int slot = i * 64 + lane, node = slot >> 1;
+                const int s = ns[node], e = ne[node];
+                const int mid = s + ((e - s) >> 1);
+                ns2[dest[i]] = (slot & 1) ? mid : s;
+                ne2[dest[i]] = (slot & 1) ? e : mid;
+            }
+        }
+        cur ^= 1;
+        wave_lds_sync();
+    }
+
+    const int *ns = nds[wave][cur];
+    for (int j = lane; j < kb; j += 64) out[j] = ns[j] * BK;
+}
+
+template <int BK, int D>
+static hipError_t launch_e(const KParams &p, dim3 grid, hipStream_t st)
+{
+    dim3 block(kThreads);
+    if (p.kb <= 128) hipLaunchKernelGGL((mask_decode_kernel<4, BK, D>), grid, block, 0, st, p);
+    else if (p.kb <= 256) hipLaunchKernelGGL((mask_decode_kernel<8, BK, D>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((mask_decode_kernel<16, BK, D>), grid, block, 0, st, p);
+    return hipGetLastError();
+}
+
+bool mask_decode_supported(const KParams &p, bool bf16)
+{
+    return bf16 && p.q_len == 1 && p.bq == 1 && (p.bk == 1 || p.bk == 2 || p.bk == 4) && p.kb <= 512;
+}
+
+hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
+{
+    const int64_t waves = (int64_t)p.batch * p.hq;
+    if (waves == 0) return hipSuccess;
+    dim3 grid((unsigned)((waves + 3) / 4));
+    if (p.d == 64) {
+        if (p.bk == 1) return launch_e<1, 64>(p, grid, st);
+        if (p.bk == 2) return launch_e<2, 64>(p, grid, st);
+        return launch_e<4, 64>(p, grid, st);
+    }
+    if (p.bk == 1) return launch_e<1, 128>(p, grid, st);
+    if (p.bk == 2) return launch_e<2, 128>(p, grid, st);
+    return launch_e<4, 128>(p, grid, st);
+}
+
+}  // namespace hipattn

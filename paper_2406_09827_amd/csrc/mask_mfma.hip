@@ -205,8 +205,7 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             }
         }
         cur ^= 1;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_sync();
     }
 
     if (wave == 0) {

@@ -59,6 +59,16 @@ def test_decode_ragged_paged(flags, integer):
     U.run_case(w, flags)
 
 
+@pytest.mark.parametrize("bk,d,k,hq,hkv", [(1, 128, 64, 4, 4), (4, 128, 1024, 8, 2), (2, 64, 256, 6, 2), (1, 64, 512, 4, 1),
+                                          (4, 64, 2048, 2, 1)])
+def test_decode_variants(bk, d, k, hq, hkv):
+    # block sizes, head dims, group sizes and k/bk (64 .. 512) the decode kernels are instantiated for
+    for integer in (True, False):
+        w = synth.Workload("decode_var", 5, hq, hkv, d, 1, 12000, k, 1, bk, "bf16", rho=0.9, ragged=(300, 12000),
+                           page_size=16 if bk == 4 else 0, integer=integer, seed=91)
+        U.run_case(w, 0)
+
+
 @pytest.mark.parametrize("flags", FLAG_SETS)
 @pytest.mark.parametrize("T,k,bq,bk,d,hq,hkv,dtype", [
     (1, 8, 1, 1, 64, 1, 1, "fp32"),        # a single token
