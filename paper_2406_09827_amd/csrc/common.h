@@ -75,15 +75,16 @@ __device__ __forceinline__ int chunk_bound(int j, int a, int r, int kb)
 }
 
 /*
- * Ordered top-kb selection among NB = 64*E keyed slots, run redundantly by every wave.
+ * Ordered top-kb selection among NB = 64*E keyed slots, run by one wave.
  *
  * Slot i*64 + lane is held by register i of `lane`.  Keeps the kb slots with the largest
  * keys (key 0 = empty slot, never kept); among equal keys the lower slot wins.  Returns for
  * each held slot whether it is kept and its rank among the kept slots in slot order, so
  * survivors can be written out compacted and still sorted by position.
  *
- * The kb-th largest key is found by a bitwise search on the key value: 32 steps, each a
- * compare per register plus a wave ballot and a scalar popcount - no sort, no barrier.
+ * The kb-th largest key is found by a bitwise search on the key value: at most 32 steps
+ * (it stops as soon as a candidate has exactly kb keys at or above it), each a compare per
+ * register plus a wave ballot and a scalar popcount - no sort, no barrier.
  */
 template <int E>
 __device__ __forceinline__ void select_topk_ordered(const uint32_t (&key)[E], int kb, bool (&keep)[E],
@@ -97,6 +98,7 @@ __device__ __forceinline__ void select_topk_ordered(const uint32_t (&key)[E], in
 #pragma unroll
         for (int i = 0; i < E; ++i) c += __popcll(__ballot(key[i] >= cand));
         if (c >= kb) v = cand;
+        if (c == kb) break;  // exactly kb keys are >= cand: the kept set is settled
     }
     int c_gt = 0;
 #pragma unroll

@@ -2,18 +2,20 @@
 // (paper Alg. 1; the block approximation of Sec. 3.2 is what makes the branch scoring a
 // dense query-block x gathered-key-rows contraction).
 //
-// One workgroup of 4 waves per (sequence, query head, query block).
-//   * The query block (<= 64 rows) sits in registers of every wave as the MFMA A operand.
-//   * A round scores 2*kb branches = 2*kb*bk gathered key rows in tiles of 32 rows; tile i
-//     goes to wave i % 4.  Every lane loads its own key row straight from global memory in
-//     the B-operand layout (lane l: row l % 32, 16-byte chunk l / 32 of each 32-byte step),
-//     the next tile's loads are in flight while the current one is multiplied.
+// Work item = one WAVE = one (sequence, query head, query block); four independent work
+// items per workgroup, no workgroup barrier and no work done twice.
+//   * The query block (<= 64 rows) sits in registers as the MFMA A operand.
+//   * A round scores 2*kb branches = 2*kb*bk gathered key rows in tiles of 32 rows.  Every
+//     lane loads its own key row straight from global memory in the B-operand layout (lane l:
+//     row l % 32, 16-byte chunk l / 32 of each 32-byte step); two register buffers alternate
+//     so the next tile's loads are in flight while the current one is multiplied.  Lanes of
+//     empty branches load row 0 of the sequence (always mapped) and drop the result, which
+//     keeps the loads unconditional.
 //   * v_mfma_f32_32x32x16_bf16 gives a 32(query) x 32(key) score tile; the branch score is
 //     the max over the admissible query rows (in-lane, then lanes l and l+32) and over the
-//     bk keys of the block (neighbouring lanes).
-//   * Scores go to LDS as order-preserving integer keys; after ONE barrier every wave runs
-//     the ordered threshold selection redundantly and writes the surviving nodes into its
-//     own private node list, so no second barrier is needed.
+//     bk keys of the block (neighbouring lanes, DPP).
+//   * Scores go to the wave's LDS slice as order-preserving integer keys; the wave runs the
+//     ordered threshold selection and writes the surviving nodes into its second node list.
 // Node ranges are block indices [s, e); the list stays sorted by position throughout, which
 // is why the result needs no sort.
 #include "common.h"
@@ -24,28 +26,12 @@ namespace hipattn {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-// (sequence, head, query block) of a workgroup.  With `xcd_map` the grid is laid out so that
-// the workgroups an XCD receives (blockIdx.x % 8) all read the same KV head, walk the query
-// blocks from the longest prefix down, and keep the query heads of a KV group adjacent.
-__device__ __forceinline__ bool decode_unit(const KParams &p, int xcd_map, int &b, int &h, int &qb)
+// max over lanes l and l ^ 32 (both get it)
+__device__ __forceinline__ float max_half_swap(float v)
 {
-    const int64_t bid = blockIdx.x;
-    const int per_group = p.g * p.nqb;
-    int64_t group, within;
-    if (xcd_map) {
-        const int xcd = (int)(bid & 7);
-        const int64_t seq = bid >> 3;
-        group = xcd + 8 * (seq / per_group);
-        within = seq % per_group;
-        if (group >= (int64_t)p.batch * p.hkv) return false;
-    } else {
-        group = bid / per_group;
-        within = bid % per_group;
-    }
-    qb = p.nqb - 1 - (int)(within / p.g);
-    h = (int)(group % p.hkv) * p.g + (int)(within % p.g);
-    b = (int)(group / p.hkv);
-    return true;
+    const unsigned u = __float_as_uint(v);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 template <int MT, int E, int D>
@@ -53,14 +39,32 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
 {
     constexpr int NB = 64 * E;  // branch slots
     constexpr int KS = D / 16;  // MFMA k-steps per key row
-    __shared__ uint32_t keys[2][NB];
+    __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
-    int b, h, qb;
-    if (!decode_unit(p, xcd_map, b, h, qb)) return;
-    const int hk = h / p.g;
+
+    // ---- which (sequence, head, query block) this wave owns.  With `xcd_map` the workgroups an
+    // XCD receives (blockIdx.x % 8) all read the same KV head; query blocks go from the longest
+    // prefix down, the query heads of a KV group are adjacent.
+    const int64_t groups = (int64_t)p.batch * p.hkv;
+    const int64_t per_group = (int64_t)p.g * p.nqb;
+    int64_t group, o;
+    if (xcd_map) {
+        const int64_t bid = blockIdx.x;
+        const int64_t seq = (bid >> 3) * 4 + wave;
+        group = (bid & 7) + 8 * (seq / per_group);
+        o = seq % per_group;
+    } else {
+        const int64_t lin = (int64_t)blockIdx.x * 4 + wave;
+        group = lin / per_group;
+        o = lin % per_group;
+    }
+    if (group >= groups) return;
+    const int qb = p.nqb - 1 - (int)(o / p.g);
+    const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
+    const int h = hk * p.g + (int)(o % p.g);
     const int kb = p.kb, bk = 1 << log_bk;
 
     const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
 
     const int Tb = L > 0 ? (L + bk - 1) >> log_bk : 0;
     if (Tb <= kb) {
-        for (int j = tid; j < kb; j += kThreads) out[j] = j < Tb ? j << log_bk : kSentinel;
+        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j << log_bk : kSentinel;
         return;
     }
 
@@ -92,7 +96,8 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
         }
     }
 
-    for (int i = tid; i < 2 * NB; i += kThreads) (&keys[0][0])[i] = 0;
+    uint32_t *keys = keys_s[wave];
+    for (int i = lane; i < NB; i += 64) keys[i] = 0;
     {
         const int a = Tb / kb, r = Tb % kb;
         for (int j = lane; j < kb; j += 64) {
@@ -100,51 +105,39 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             nde[wave][0][j] = chunk_bound(j + 1, a, r, kb);
         }
     }
-    __syncthreads();
+    wave_lds_sync();
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     const int n_tiles = (2 * kb * bk + 31) >> 5;
     const bool full_rows = n_rows == 32 * MT;
-    int cur = 0, round = 0;
+    int cur = 0;
 
-    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1, ++round) {
+    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         const int *ns = nds[wave][cur], *ne = nde[wave][cur];
-        uint32_t *kout = keys[round & 1];
 
-        // metadata + loads of one tile of 32 gathered key rows
-        auto fetch = [&](int tile, uint4(&kr)[KS], int &t, int &slot, bool &slot_ok, bool &row_ok) {
+        // metadata + loads of one tile of 32 gathered key rows.  tinfo packs the key position
+        // (or -1 when this lane's row does not count) and slot_ok in the sign of `slot`.
+        auto fetch = [&](int tile, uint4(&kr)[KS], int &t, int &slot) {
             const int rr = tile * 32 + col;
-            slot = rr >> log_bk;
-            const int node = slot >> 1;
-            slot_ok = node < kb;
-            t = 0;
+            const int sl = rr >> log_bk, node = sl >> 1;
+            bool slot_ok = node < kb;
+            int tt = 0;
             if (slot_ok) {
                 const int s = ns[node], e = ne[node];
                 const int mid = s + ((e - s) >> 1);
-                const int bs = (slot & 1) ? mid : s, be = (slot & 1) ? e : mid;
+                const int bs = (sl & 1) ? mid : s, be = (sl & 1) ? e : mid;
                 slot_ok = be > bs;
-                t = ((bs + ((be - bs) >> 1)) << log_bk) + (rr & (bk - 1));
+                tt = ((bs + ((be - bs) >> 1)) << log_bk) + (rr & (bk - 1));
             }
-            row_ok = slot_ok && t < kv_len;
-            if (row_ok) {
-                const bf16_t *src = Kbase + kv_row_offset(p, b, hk, t) + hh * 8;
+            const bool row_ok = slot_ok && tt < kv_len;
+            t = row_ok ? tt : -1;
+            slot = slot_ok ? sl : ~sl;  // negative = empty branch (still names the slot to clear)
+            const bf16_t *src = Kbase + kv_row_offset(p, b, hk, row_ok ? tt : 0) + hh * 8;
 #pragma unroll
-                for (int kk = 0; kk < KS; ++kk) kr[kk] = *(const uint4 *)(src + kk * 16);
-            } else {
-#pragma unroll
-                for (int kk = 0; kk < KS; ++kk) kr[kk] = make_uint4(0, 0, 0, 0);
-            }
+            for (int kk = 0; kk < KS; ++kk) kr[kk] = *(const uint4 *)(src + kk * 16);
         };
 
-        uint4 kc[KS], kn[KS];
-        int t_c, slot_c, t_n = 0, slot_n = 0;
-        bool sok_c, rok_c, sok_n = false, rok_n = false;
-        int tile = wave;
-        if (tile < n_tiles) fetch(tile, kc, t_c, slot_c, sok_c, rok_c);
-        for (; tile < n_tiles; tile += 4) {
-            const bool has_next = tile + 4 < n_tiles;
-            if (has_next) fetch(tile + 4, kn, t_n, slot_n, sok_n, rok_n);
-
+        auto score = [&](const uint4(&kr)[KS], int t, int slot) {
             f32x16 acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -154,12 +147,12 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kc[kk]),
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kr[kk]),
                                                                       acc[mt], 0, 0, 0);
             // max over the admissible query rows of this lane's key column
-            const int lo = t_c - pos0;  // rows i < lo would look into the future
+            const int lo = t - pos0;  // rows i < lo would look into the future
             float v = -INFINITY;
-            if (full_rows && __ballot(rok_c && lo > 0) == 0) {
+            if (full_rows && __ballot(lo > 0) == 0) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -173,25 +166,36 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
                         if (i >= lo && i < n_rows) v = fmaxf(v, acc[mt][r]);
                     }
             }
-            if (!rok_c) v = -INFINITY;
-            v = fmaxf(v, __shfl_xor(v, 32, 64));
-            for (int o = 1; o < bk; o <<= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-            if (hh == 0 && (col & (bk - 1)) == 0 && slot_c < NB) kout[slot_c] = sok_c ? score_key(v) : 0u;
+            if (t < 0) v = -INFINITY;
+            v = max_half_swap(v);
+            if (log_bk >= 1) v = fmaxf(v, dpp_f<0xB1>(v));   // lane ^ 1
+            if (log_bk >= 2) v = fmaxf(v, dpp_f<0x4E>(v));   // lane ^ 2
+            if (log_bk >= 3) v = fmaxf(v, dpp_f<0x141>(v));  // other quad of the 8 (row_half_mirror)
+            if (log_bk >= 4) v = fmaxf(v, dpp_f<0x140>(v));  // other 8 of the 16 (row_mirror)
+            const int sl = slot < 0 ? ~slot : slot;
+            if (hh == 0 && (col & (bk - 1)) == 0 && sl < NB) keys[sl] = slot < 0 ? 0u : score_key(v);
+        };
 
-            if (has_next) {
-#pragma unroll
-                for (int kk = 0; kk < KS; ++kk) kc[kk] = kn[kk];
-                t_c = t_n; slot_c = slot_n; sok_c = sok_n; rok_c = rok_n;
+        uint4 ka[KS], kbuf[KS];
+        int t_a, s_a, t_b, s_b;
+        fetch(0, ka, t_a, s_a);
+        for (int tile = 0; tile < n_tiles; tile += 2) {
+            const bool has_b = tile + 1 < n_tiles;
+            if (has_b) fetch(tile + 1, kbuf, t_b, s_b);
+            score(ka, t_a, s_a);
+            if (has_b) {
+                if (tile + 2 < n_tiles) fetch(tile + 2, ka, t_a, s_a);
+                score(kbuf, t_b, s_b);
             }
         }
-        __syncthreads();
+        wave_lds_sync();
 
-        // selection, redundantly per wave, into this wave's private next node list
+        // ordered top-kb selection into this wave's other node list
         uint32_t key[E];
         bool keep[E];
         int dest[E];
 #pragma unroll
-        for (int i = 0; i < E; ++i) key[i] = kout[i * 64 + lane];
+        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
         select_topk_ordered<E>(key, kb, keep, dest);
         int *ns2 = nds[wave][cur ^ 1], *ne2 = nde[wave][cur ^ 1];
 #pragma unroll
@@ -208,10 +212,8 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
         wave_lds_sync();
     }
 
-    if (wave == 0) {
-        const int *ns = nds[0][cur];
-        for (int j = lane; j < kb; j += 64) out[j] = ns[j] << log_bk;
-    }
+    const int *ns = nds[wave][cur];
+    for (int j = lane; j < kb; j += 64) out[j] = ns[j] << log_bk;
 }
 
 template <int MT, int D>
@@ -236,10 +238,10 @@ hipError_t launch_mask_mfma(const KParams &p, hipStream_t st)
     while ((1 << log_bk) < p.bk) ++log_bk;
     const int64_t groups = (int64_t)p.batch * p.hkv;
     const int64_t per_group = (int64_t)p.g * p.nqb;
-    const int xcd_map = groups % 8 == 0 ? 1 : 0;
+    const int xcd_map = (groups % 8 == 0 && per_group % 4 == 0) ? 1 : 0;
     const int64_t units = groups * per_group;
     if (units == 0) return hipSuccess;
-    dim3 grid((unsigned)units);
+    dim3 grid((unsigned)((units + 3) / 4));
     if (p.bq <= 32) return p.d == 64 ? launch_e<1, 64>(p, log_bk, xcd_map, grid, st) : launch_e<1, 128>(p, log_bk, xcd_map, grid, st);
     return p.d == 64 ? launch_e<2, 64>(p, log_bk, xcd_map, grid, st) : launch_e<2, 128>(p, log_bk, xcd_map, grid, st);
 }
