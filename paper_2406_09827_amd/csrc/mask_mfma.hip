@@ -5,12 +5,14 @@
 // Work item = one WAVE = one (sequence, query head, query block); four independent work
 // items per workgroup, no workgroup barrier and no work done twice.
 //   * The query block (<= 64 rows) sits in registers as the MFMA A operand.
-//   * A round scores 2*kb branches = 2*kb*bk gathered key rows in tiles of 32 rows.  Every
-//     lane loads its own key row straight from global memory in the B-operand layout (lane l:
-//     row l % 32, 16-byte chunk l / 32 of each 32-byte step); two register buffers alternate
-//     so the next tile's loads are in flight while the current one is multiplied.  Lanes of
-//     empty branches load row 0 of the sequence (always mapped) and drop the result, which
-//     keeps the loads unconditional.
+//   * A round scores 2*kb branches = 2*kb*bk gathered key rows in tiles of 32 rows.  The rows
+//     are loaded COALESCED (a row = D/8 consecutive lanes x 16 bytes, so the address unit sees
+//     whole cache lines instead of 64 separate ones), parked in two alternating register sets
+//     while in flight (two tiles ahead), written into the wave's LDS tile with an XOR swizzle
+//     and read back in the MFMA B-operand layout (lane l: row l % 32, 16-byte chunk l / 32 of
+//     each 32-byte step) without bank conflicts.  Row offsets are worked out once per row and
+//     handed to the loading lanes through a 32-entry LDS table.  Rows of empty branches load
+//     row 0 of the sequence (always mapped) and drop the result: loads stay unconditional.
 //   * v_mfma_f32_32x32x16_bf16 gives a 32(query) x 32(key) score tile; the branch score is
 //     the max over the admissible query rows (in-lane, then lanes l and l+32) and over the
 //     bk keys of the block (neighbouring lanes, DPP).
@@ -41,6 +43,8 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
     constexpr int KS = D / 16;  // MFMA k-steps per key row
     __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
+    __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
+    __shared__ __attribute__((aligned(16))) uint32_t meta_s[4][32];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
@@ -96,7 +100,14 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
         }
     }
 
+    constexpr int CPR = D / 8;     // 16-byte chunks per key row
+    constexpr int RPI = 64 / CPR;  // rows per wave-wide load
+    constexpr int NLD = 32 / RPI;  // loads per lane and tile
+    constexpr int ROWB = D * 2;    // bytes per row
+    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * NLD)));
     uint32_t *keys = keys_s[wave];
+    char *tile_s = (char *)tile_buf[wave];
+    uint32_t *meta = meta_s[wave];
     for (int i = lane; i < NB; i += 64) keys[i] = 0;
     {
         const int a = Tb / kb, r = Tb % kb;
@@ -110,14 +121,16 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
     const bf16_t *Kbase = (const bf16_t *)p.K;
     const int n_tiles = (2 * kb * bk + 31) >> 5;
     const bool full_rows = n_rows == 32 * MT;
+    const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
     int cur = 0;
 
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         const int *ns = nds[wave][cur], *ne = nde[wave][cur];
 
-        // metadata + loads of one tile of 32 gathered key rows.  tinfo packs the key position
-        // (or -1 when this lane's row does not count) and slot_ok in the sign of `slot`.
-        auto fetch = [&](int tile, uint4(&kr)[KS], int &t, int &slot) {
+        // Row metadata of one tile (lane = row col) and the coalesced loads of its 32 rows.
+        // t = key position of this lane's row, or -1 if the row does not count;
+        // slot = branch slot, complemented when the branch is empty.
+        auto fetch = [&](int tile, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
             const int rr = tile * 32 + col;
             const int sl = rr >> log_bk, node = sl >> 1;
             bool slot_ok = node < kb;
@@ -131,24 +144,47 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             }
             const bool row_ok = slot_ok && tt < kv_len;
             t = row_ok ? tt : -1;
-            slot = slot_ok ? sl : ~sl;  // negative = empty branch (still names the slot to clear)
-            const bf16_t *src = Kbase + kv_row_offset(p, b, hk, row_ok ? tt : 0) + hh * 8;
+            slot = slot_ok ? sl : ~sl;
+            // row offset in 16-byte units (strides are multiples of 8 elements)
+            if (hh == 0) meta[col] = (uint32_t)(kv_row_offset(p, b, hk, row_ok ? tt : 0) >> 3);
+            wave_lds_sync();
+            uint32_t off[NLD];
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) kr[kk] = *(const uint4 *)(src + kk * 16);
+            for (int j = 0; j < NLD; j += 4) {
+                const uint4 m4 = *(const uint4 *)(meta + lg * NLD + j);
+                off[j] = m4.x; off[j + 1] = m4.y; off[j + 2] = m4.z; off[j + 3] = m4.w;
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const uint4 x = *(const uint4 *)(Kbase + ((int64_t)off[j] << 3) + lc * 8);
+                R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
+            }
         };
 
-        auto score = [&](const uint4(&kr)[KS], int t, int slot) {
+        // registers -> swizzled LDS tile: row r = lg*NLD + j, chunk lc goes to slot lc ^ (r % CPR)
+        auto park = [&](const stage_t &R) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                const int r = lg * NLD + j;
+                *(uint4 *)(tile_s + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) =
+                    make_uint4(R[4 * j], R[4 * j + 1], R[4 * j + 2], R[4 * j + 3]);
+            }
+        };
+
+        auto score = [&](int t, int slot) __attribute__((always_inline)) {
             f32x16 acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
+            for (int kk = 0; kk < KS; ++kk) {
+                const uint4 kv = *(const uint4 *)(tile_s + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kr[kk]),
-                                                                      acc[mt], 0, 0, 0);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv), acc[mt], 0, 0, 0);
+            }
             // max over the admissible query rows of this lane's key column
             const int lo = t - pos0;  // rows i < lo would look into the future
             float v = -INFINITY;
@@ -176,16 +212,26 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             if (hh == 0 && (col & (bk - 1)) == 0 && sl < NB) keys[sl] = slot < 0 ? 0u : score_key(v);
         };
 
-        uint4 ka[KS], kbuf[KS];
-        int t_a, s_a, t_b, s_b;
-        fetch(0, ka, t_a, s_a);
+        stage_t R0, R1;  // one vector value each, so the staged rows stay in registers
+        int t0 = -1, s0 = ~0, t1 = -1, s1 = ~0;
+        fetch(0, R0, t0, s0);
+        if (n_tiles > 1) fetch(1, R1, t1, s1);
         for (int tile = 0; tile < n_tiles; tile += 2) {
-            const bool has_b = tile + 1 < n_tiles;
-            if (has_b) fetch(tile + 1, kbuf, t_b, s_b);
-            score(ka, t_a, s_a);
-            if (has_b) {
-                if (tile + 2 < n_tiles) fetch(tile + 2, ka, t_a, s_a);
-                score(kbuf, t_b, s_b);
+            {
+                const int tc = t0, sc = s0;
+                park(R0);
+                if (tile + 2 < n_tiles) fetch(tile + 2, R0, t0, s0);
+                wave_lds_sync();
+                score(tc, sc);
+                wave_lds_sync();
+            }
+            if (tile + 1 < n_tiles) {
+                const int tc = t1, sc = s1;
+                park(R1);
+                if (tile + 3 < n_tiles) fetch(tile + 3, R1, t1, s1);
+                wave_lds_sync();
+                score(tc, sc);
+                wave_lds_sync();
             }
         }
         wave_lds_sync();
