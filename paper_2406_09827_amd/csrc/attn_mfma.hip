@@ -4,8 +4,9 @@
 // Work item = one wave = one (sequence, query head, query block, 32-row query tile); four
 // independent work items per workgroup, no workgroup barrier anywhere.
 // Per tile of 32 gathered keys:
-//   S^T = K_tile . Q^T     v_mfma_f32_32x32x16_bf16, A = key rows loaded straight from global
-//                          memory (lane = key row), B = the query tile held in registers.
+//   S^T = K_tile . Q^T     v_mfma_f32_32x32x16_bf16, A = key rows (loaded coalesced, staged in a
+//                          swizzled LDS tile, read back one row per lane), B = the query tile
+//                          held in registers.
 //                          The result has one query per lane and 16 keys in its registers,
 //                          so the softmax statistics of a query are lane-local (plus one
 //                          exchange with lane ^ 32) and P^T is already in B-operand layout.
@@ -31,20 +32,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 }
 
 template <int D>
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
 {
     constexpr int KS = D / 16;     // k-steps of S^T = K Q^T
     constexpr int CT = D / 32;     // 32-channel tiles of O^T
-    constexpr int PITCH = D + 8;   // LDS row pitch in bf16: 16 bytes of padding per row
+    constexpr int PITCH = D + 8;   // value tile row pitch in bf16: 16 bytes of padding per row
     constexpr int CPR = D / 8;     // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;  // rows covered by one wave-wide 16-byte load
     constexpr int NLD = 32 / RPI;  // such loads per 32-row tile
+    constexpr int ROWB = D * 2;    // bytes per key row in the (swizzled, unpadded) key tile
+    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * NLD)));
     __shared__ __attribute__((aligned(16))) bf16_t vt_s[4][32 * PITCH];
-    __shared__ __attribute__((aligned(16))) int tk_s[4][32];
-    __shared__ __attribute__((aligned(16))) int64_t vo_s[4][32];
+    __shared__ __attribute__((aligned(16))) uint4 kt_s[4][32 * ROWB / 16];
+    __shared__ __attribute__((aligned(16))) int tk_s[4][2][32];
+    __shared__ __attribute__((aligned(16))) uint32_t mo_s[4][32];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
+    const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
 
     // ---- which (sequence, head, query block, query tile) this wave owns
     const int64_t groups = (int64_t)p.batch * p.hkv;
@@ -89,8 +94,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(KParams p, int log_
 
     const bf16_t *Kbase = (const bf16_t *)p.K, *Vbase = (const bf16_t *)p.V;
     bf16_t *vt = vt_s[wave];
-    int *tk = tk_s[wave];
-    int64_t *vo = vo_s[wave];
+    char *kt = (char *)kt_s[wave];
+    uint32_t *mo = mo_s[wave];
 
     const float c = p.sm_scale * 1.44269504088896340736f;  // scores are kept in log2 units
     float m_run = -INFINITY, l_run = 0.f;
@@ -100,132 +105,145 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(KParams p, int log_
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[ct][r] = 0.f;
 
-    // key row `col` of a tile: logical position (or -1), row offset, and its K data
-    uint4 kr[KS];
-    int t_c;
-    int64_t off_c;
-    auto fetch_k = [&](int tile) {
+    // One tile of 32 gathered keys: lane `col` works out key row col (position or -1, row
+    // offset in 16-byte units), publishes both, then every lane loads its share of the key and
+    // value rows coalesced.  Rows that do not count load row 0 of the sequence (always mapped,
+    // finite) and get probability 0.  Returns flags: bit 0 = some key is visible to some row,
+    // bit 1 = some (key, row) pair needs masking.
+    auto fetch = [&](int tile, stage_t &RK, stage_t &RV, int *tk) __attribute__((always_inline)) {
         const int ki = tile * 32 + col;
-        t_c = -1;
-        off_c = 0;
+        int t_c = -1;
         if (ki < n_keys) {
             const int first = idx[ki >> log_bk];
             const int t = first + (ki & (bk - 1));
             if (first >= 0 && first < kv_len && t < kv_len) t_c = t;
         }
-        if (t_c >= 0) {
-            off_c = kv_row_offset(p, b, hk, t_c);
-            const bf16_t *src = Kbase + off_c + hh * 8;
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) kr[kk] = *(const uint4 *)(src + kk * 16);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < KS; ++kk) kr[kk] = make_uint4(0, 0, 0, 0);
+        if (hh == 0) {
+            tk[col] = t_c;
+            mo[col] = (uint32_t)(kv_row_offset(p, b, hk, t_c >= 0 ? t_c : 0) >> 3);
         }
+        const int flags = (__ballot(t_c >= 0 && t_c <= pos0 + n_rows - 1) != 0 ? 1 : 0) |
+                          (__ballot(t_c < 0 || t_c > pos0) != 0 ? 2 : 0);
+        wave_lds_sync();
+        uint32_t off[NLD];
+#pragma unroll
+        for (int j = 0; j < NLD; j += 4) {
+            const uint4 m4 = *(const uint4 *)(mo + lg * NLD + j);
+            off[j] = m4.x; off[j + 1] = m4.y; off[j + 2] = m4.z; off[j + 3] = m4.w;
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int64_t eo = ((int64_t)off[j] << 3) + lc * 8;
+            const uint4 x = *(const uint4 *)(Kbase + eo);
+            const uint4 y = *(const uint4 *)(Vbase + eo);
+            RK[4 * j] = x.x; RK[4 * j + 1] = x.y; RK[4 * j + 2] = x.z; RK[4 * j + 3] = x.w;
+            RV[4 * j] = y.x; RV[4 * j + 1] = y.y; RV[4 * j + 2] = y.z; RV[4 * j + 3] = y.w;
+        }
+        return flags;
     };
 
-    fetch_k(0);
+    stage_t RK, RV;
+    int flags_next = fetch(0, RK, RV, tk_s[wave][0]);
     for (int tile = 0; tile < n_tiles; ++tile) {
-        const bool any_valid = __ballot(t_c >= 0 && t_c <= pos0 + n_rows - 1) != 0;
-        if (hh == 0) { tk[col] = t_c; vo[col] = off_c; }
+        const int flags = flags_next;
+        const int *tk = tk_s[wave][tile & 1];
+        // registers -> LDS: key tile swizzled (chunk lc of row r at slot lc ^ (r % CPR)), value tile padded
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int r = lg * NLD + j;
+            *(uint4 *)(kt + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) = make_uint4(RK[4 * j], RK[4 * j + 1], RK[4 * j + 2], RK[4 * j + 3]);
+            *(uint4 *)(vt + r * PITCH + lc * 8) = make_uint4(RV[4 * j], RV[4 * j + 1], RV[4 * j + 2], RV[4 * j + 3]);
+        }
+        if (tile + 1 < n_tiles) flags_next = fetch(tile + 1, RK, RV, tk_s[wave][(tile + 1) & 1]);
         wave_lds_sync();
 
-        uint4 vr[NLD];
-        f32x16 sacc;
-        if (any_valid) {
-            // value rows of this tile, coalesced: 16-byte chunk (lane % CPR) of row lane / CPR + i*RPI
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                const int row = lane / CPR + i * RPI;
-                vr[i] = make_uint4(0, 0, 0, 0);
-                if (tk[row] >= 0) vr[i] = *(const uint4 *)(Vbase + vo[row] + (lane % CPR) * 8);
-            }
+        if (flags & 1) {
+            // ---- S^T = K Q^T: A = key rows from the LDS tile (lane: key row col), B = queries
+            f32x16 sacc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kr[kk]), qf[kk], sacc, 0, 0, 0);
-        }
-        // positions of the 16 keys this lane holds scores for: rows 8g + 4hh + {0..3}
-        int4 tq[4];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) tq[g] = *(const int4 *)(tk + 8 * g + 4 * hh);
-        wave_lds_sync();  // tk/vo are consumed; the next fetch may overwrite nothing yet, but keep order
-
-        if (tile + 1 < n_tiles) fetch_k(tile + 1);  // next keys in flight during softmax and P.V
-        if (!any_valid) continue;
-
-        // ---- online softmax for query `col` (both half-waves hold the same query)
-        const int qpos = pos0 + col;
-        float s[16], mx = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int g = r >> 2;
-            const int tkey = (r & 3) == 0 ? tq[g].x : (r & 3) == 1 ? tq[g].y : (r & 3) == 2 ? tq[g].z : tq[g].w;
-            const bool ok = tkey >= 0 && tkey <= qpos;
-            s[r] = ok ? sacc[r] * c : -INFINITY;
-            mx = fmaxf(mx, s[r]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        float lsum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            s[r] = __builtin_amdgcn_exp2f(s[r] - m_safe);
-            lsum += s[r];
-        }
-        l_run = l_run * alpha + lsum;
-        m_run = m_new;
-        if (__ballot(alpha != 1.f) != 0) {
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[ct][r] *= alpha;
-        }
-        // P^T as B operand of the two 16-key steps (registers 8*st .. 8*st+7), carried as a
-        // two-term bf16 expansion p = hi + lo so that rounding P does not limit the output
-        bf16x8 pb[2], pl[2];
-#pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const float a0 = s[8 * st + 2 * e2], a1 = s[8 * st + 2 * e2 + 1];
-                hi[e2] = pack_bf16(a0, a1);
-                lo[e2] = pack_bf16(a0 - __uint_as_float(hi[e2] << 16), a1 - __uint_as_float(hi[e2] & 0xffff0000u));
+            for (int kk = 0; kk < KS; ++kk) {
+                const uint4 kv = *(const uint4 *)(kt + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[kk], sacc, 0, 0, 0);
             }
-            pb[st] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-            pl[st] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-        }
 
-        // ---- stage V in LDS, read it back channel-major, O^T += V^T P^T
+            // ---- online softmax for query `col` (both half-waves hold the same query)
+            float s[16], mx = -INFINITY;
+            if (flags & 2) {
+                // positions of the 16 keys this lane holds scores for: rows 8g + 4hh + {0..3}
+                const int qpos = pos0 + col;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int row = lane / CPR + i * RPI;
-            *(uint4 *)(vt + row * PITCH + (lane % CPR) * 8) = vr[i];
-        }
-        wave_lds_sync();
+                for (int g = 0; g < 4; ++g) {
+                    const int4 tq = *(const int4 *)(tk + 8 * g + 4 * hh);
+                    const int tkey[4] = {tq.x, tq.y, tq.z, tq.w};
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
+                    for (int e = 0; e < 4; ++e) {
+                        const bool ok = tkey[e] >= 0 && tkey[e] <= qpos;
+                        s[4 * g + e] = ok ? sacc[4 * g + e] * c : -INFINITY;
+                    }
+                }
+            } else {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                // A operand: channel ct*32 + col, keys (2st + e/4)*8 + 4hh + e%4, e = 0..7
-                const bf16_t *src = vt + ((2 * st) * 8 + 4 * hh) * PITCH + ct * 32 + col;
-                uint32_t w[4];
+                for (int r = 0; r < 16; ++r) s[r] = sacc[r] * c;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+            float lsum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                s[r] = __builtin_amdgcn_exp2f(s[r] - m_safe);
+                lsum += s[r];
+            }
+            l_run = l_run * alpha + lsum;
+            m_run = m_new;
+            if (__ballot(alpha != 1.f) != 0) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[ct][r] *= alpha;
+            }
+            // P^T as B operand of the two 16-key steps (registers 8*st .. 8*st+7), carried as a
+            // two-term bf16 expansion p = hi + lo so that rounding P does not limit the output
+            bf16x8 pb[2], pl[2];
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int e2 = 0; e2 < 4; ++e2) {
-                    const int k0 = ((2 * e2) >> 2) * 8 + ((2 * e2) & 3);
-                    w[e2] = (uint32_t)src[k0 * PITCH] | ((uint32_t)src[(k0 + 1) * PITCH] << 16);
+                    const float a0 = s[8 * st + 2 * e2], a1 = s[8 * st + 2 * e2 + 1];
+                    hi[e2] = pack_bf16(a0, a1);
+                    lo[e2] = pack_bf16(a0 - __uint_as_float(hi[e2] << 16), a1 - __uint_as_float(hi[e2] & 0xffff0000u));
                 }
-                uint4 u = make_uint4(w[0], w[1], w[2], w[3]);
-                const bf16x8 va = __builtin_bit_cast(bf16x8, u);
-                oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
-                oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
+                pb[st] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+                pl[st] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+            }
+
+            // ---- O^T += V^T P^T: value tile read back channel-major
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    // A operand: channel ct*32 + col, keys (2st + e/4)*8 + 4hh + e%4, e = 0..7
+                    const bf16_t *src = vt + ((2 * st) * 8 + 4 * hh) * PITCH + ct * 32 + col;
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const int k0 = ((2 * e2) >> 2) * 8 + ((2 * e2) & 3);
+                        w[e2] = (uint32_t)src[k0 * PITCH] | ((uint32_t)src[(k0 + 1) * PITCH] << 16);
+                    }
+                    const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+                    oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
+                    oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
+                }
             }
         }
-        wave_lds_sync();
+        wave_lds_sync();  // the tiles are consumed before the next iteration overwrites them
     }
 
     // ---- normalise, transpose through LDS, coalesced store
