@@ -16,7 +16,8 @@ template <int BK, int D>
 __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 {
     constexpr int LPR = D / 8, RPW = 64 / LPR;
-    constexpr int U = BK >= 4 ? 1 : 4 / BK;  // blocks in flight per lane group (4 key + 4 value rows)
+    constexpr int U = 8 / BK;  // blocks per lane group and stage: 8 key + 8 value row loads per lane, two stages in flight
+    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, lc = lane % LPR;
     const int64_t wg = (int64_t)blockIdx.x * 4 + wave;
@@ -34,35 +35,39 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-    for (int base = 0; base < kb; base += RPW * U) {
-        uint4 kr[U][BK], vr[U][BK];
-        bool ok[U][BK];
+    // one stage = U blocks per lane group: BK key rows and BK value rows each, loaded
+    // unconditionally (a block that does not count re-reads row 0 and gets probability 0).
+    auto fetch = [&](int base, stage_t &kr, stage_t &vr, int (&first)[U]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * RPW + grp;
-            int first = -1;
-            if (j < kb) first = idx[j];
-            const bool blk = first >= 0 && first < kv_len;
-            int64_t off = 0;
-            if (blk) off = kv_row_offset(p, b, hk, first) + lc * 8;
+            int f = -1;
+            if (j < kb) f = idx[j];
+            if (f >= kv_len) f = -1;
+            first[u] = f;
+            const int64_t off = kv_row_offset(p, b, hk, f >= 0 ? f : 0) + lc * 8;
 #pragma unroll
             for (int n = 0; n < BK; ++n) {
-                ok[u][n] = blk && first + n < kv_len;  // the query is the last position: no key is in its future
-                kr[u][n] = make_uint4(0, 0, 0, 0);
-                vr[u][n] = make_uint4(0, 0, 0, 0);
-                if (ok[u][n]) {
-                    kr[u][n] = *(const uint4 *)(Kbase + off + (int64_t)n * p.ks_r);
-                    vr[u][n] = *(const uint4 *)(Vbase + off + (int64_t)n * p.ks_r);
-                }
+                const int dn = f >= 0 ? min(n, kv_len - 1 - f) : 0;
+                const uint4 x = *(const uint4 *)(Kbase + off + (int64_t)dn * p.ks_r);
+                const uint4 y = *(const uint4 *)(Vbase + off + (int64_t)dn * p.ks_r);
+                const int q4 = 4 * (u * BK + n);
+                kr[q4] = x.x; kr[q4 + 1] = x.y; kr[q4 + 2] = x.z; kr[q4 + 3] = x.w;
+                vr[q4] = y.x; vr[q4 + 1] = y.y; vr[q4 + 2] = y.z; vr[q4 + 3] = y.w;
             }
         }
+    };
+    auto consume = [&](const stage_t &kr, const stage_t &vr, const int (&first)[U]) __attribute__((always_inline)) {
         float s[U][BK], mx = -INFINITY;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int n = 0; n < BK; ++n) {
-                const float d = row_group_sum<LPR>(dot8_bf16(qv, kr[u][n])) * c;
-                s[u][n] = ok[u][n] ? d : -INFINITY;
+                const int q4 = 4 * (u * BK + n);
+                const float d = row_group_sum<LPR>(dot8_bf16(qv, make_uint4(kr[q4], kr[q4 + 1], kr[q4 + 2], kr[q4 + 3]))) * c;
+                // the query is the last position of its sequence: no key is in its future
+                const bool ok = first[u] >= 0 && first[u] + n < kv_len;
+                s[u][n] = ok ? d : -INFINITY;
                 mx = fmaxf(mx, s[u][n]);
             }
         const float m_new = fmaxf(m_run, mx);
@@ -77,14 +82,28 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
             for (int n = 0; n < BK; ++n) {
                 const float pr = __builtin_amdgcn_exp2f(s[u][n] - m_safe);
                 l_run += pr;
-                const uint32_t w[4] = {vr[u][n].x, vr[u][n].y, vr[u][n].z, vr[u][n].w};
+                const int q4 = 4 * (u * BK + n);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] = fmaf(pr, __uint_as_float(w[i] << 16), acc[2 * i]);
-                    acc[2 * i + 1] = fmaf(pr, __uint_as_float(w[i] & 0xffff0000u), acc[2 * i + 1]);
+                    acc[2 * i] = fmaf(pr, __uint_as_float(vr[q4 + i] << 16), acc[2 * i]);
+                    acc[2 * i + 1] = fmaf(pr, __uint_as_float(vr[q4 + i] & 0xffff0000u), acc[2 * i + 1]);
                 }
             }
         m_run = m_new;
+    };
+
+    constexpr int STEP = RPW * U;
+    stage_t ka, va, kb2, vb2;
+    int fa[U], fb[U];
+    fetch(0, ka, va, fa);
+    for (int base = 0; base < kb; base += 2 * STEP) {
+        const bool has_b = base + STEP < kb;
+        if (has_b) fetch(base + STEP, kb2, vb2, fb);
+        consume(ka, va, fa);
+        if (has_b) {
+            if (base + 2 * STEP < kb) fetch(base + 2 * STEP, ka, va, fa);
+            consume(kb2, vb2, fb);
+        }
     }
 
     // merge the lane groups' partial softmax states (same channels, different keys)

@@ -8,7 +8,9 @@
 // L1/L2 instead of going to HBM four times.
 //   * a key row is read by D/8 lanes, 16 bytes each (a full 128-bit coalesced row segment),
 //     multiplied with v_dot2_f32_bf16 and summed over the lanes with DPP adds;
-//   * several blocks per lane group are in flight at once (8 loads per lane);
+//   * two stages of 16 row loads per lane alternate, so up to 32 KB per wave are in flight
+//     (a wave is alone on its SIMD at small batch, the memory pipeline has to be kept full
+//     from inside the wave);
 //   * scores -> per-wave LDS keys -> ordered threshold selection (once per wave, nothing
 //     redundant) -> the wave's private node list.  No workgroup barrier anywhere.
 // Ragged lengths (kv_lens) and a page table are handled per row.
@@ -23,7 +25,8 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     constexpr int NB = 64 * E;
     constexpr int LPR = D / 8;        // lanes per key row
     constexpr int RPW = 64 / LPR;     // rows (= branches) per wave-wide load
-    constexpr int U = BK >= 8 ? 1 : 8 / BK;  // branches in flight per lane group
+    constexpr int U = 16 / BK;        // branches per lane group and stage: 16 row loads per lane, two stages in flight
+    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
 
@@ -59,40 +62,59 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         const int *ns = nds[wave][cur], *ne = nde[wave][cur];
 
-        for (int base = 0; base < 2 * kb; base += RPW * U) {
-            uint4 kv[U][BK];
-            bool ok[U];
-            int t0[U];
+        // one stage = U branches per lane group: node lookup, then the (unconditional) loads of
+        // the representative block's BK rows.  t0 < 0 marks an empty branch.
+        auto fetch = [&](int base, stage_t &kv, int (&t0)[U]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int slot = base + u * RPW + grp, node = slot >> 1;
-                ok[u] = node < kb;
-                t0[u] = 0;
-                if (ok[u]) {
+                bool ok = node < kb;
+                int t = 0;
+                if (ok) {
                     const int s = ns[node], e = ne[node];
                     const int mid = s + ((e - s) >> 1);
                     const int bs = (slot & 1) ? mid : s, be = (slot & 1) ? e : mid;
-                    ok[u] = be > bs;
-                    t0[u] = (bs + ((be - bs) >> 1)) * BK;
+                    ok = be > bs;
+                    t = (bs + ((be - bs) >> 1)) * BK;
                 }
-                const bf16_t *src = nullptr;
-                if (ok[u]) src = Kbase + kv_row_offset(p, b, hk, t0[u]) + lc * 8;
+                t0[u] = ok ? t : -1;
+                const bf16_t *src = Kbase + kv_row_offset(p, b, hk, ok ? t : 0) + lc * 8;
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
-                    kv[u][n] = make_uint4(0, 0, 0, 0);
-                    if (ok[u] && t0[u] + n < kv_len) kv[u][n] = *(const uint4 *)(src + (int64_t)n * p.ks_r);
+                    // rows past the end of the sequence re-read its last row and are ignored below
+                    const int dn = ok ? min(n, kv_len - 1 - t) : 0;
+                    const uint4 x = *(const uint4 *)(src + (int64_t)dn * p.ks_r);
+                    const int q4 = 4 * (u * BK + n);
+                    kv[q4] = x.x; kv[q4 + 1] = x.y; kv[q4 + 2] = x.z; kv[q4 + 3] = x.w;
                 }
             }
+        };
+        auto score = [&](int base, const stage_t &kv, const int (&t0)[U]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float best = -INFINITY;
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
-                    const float dsum = row_group_sum<LPR>(dot8_bf16(qv, kv[u][n]));
+                    const int q4 = 4 * (u * BK + n);
+                    const float dsum = row_group_sum<LPR>(dot8_bf16(qv, make_uint4(kv[q4], kv[q4 + 1], kv[q4 + 2], kv[q4 + 3])));
                     if (t0[u] + n < kv_len) best = fmaxf(best, dsum);
                 }
                 const int slot = base + u * RPW + grp;
-                if (lc == 0 && slot < NB) keys[slot] = ok[u] ? score_key(best) : 0u;
+                if (lc == 0 && slot < NB) keys[slot] = t0[u] >= 0 ? score_key(best) : 0u;
+            }
+        };
+
+        constexpr int STEP = RPW * U;
+        stage_t ka, kbuf;
+        int ta[U], tb[U];
+        fetch(0, ka, ta);
+        for (int base = 0; base < 2 * kb; base += 2 * STEP) {
+            const bool has_b = base + STEP < 2 * kb;
+            if (has_b) fetch(base + STEP, kbuf, tb);
+            score(base, ka, ta);
+            if (has_b) {
+                if (base + 2 * STEP < 2 * kb) fetch(base + 2 * STEP, ka, ta);
+                score(base + STEP, kbuf, tb);
             }
         }
         wave_lds_sync();
