@@ -35,6 +35,9 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.kb = p.k / p.bk; kp.bq = p.bq; kp.bk = p.bk; kp.nqb = nqb;
     kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
+    kp.page_shift = -1;
+    if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
+        for (kp.page_shift = 0; (1 << kp.page_shift) < p.page_size;) ++kp.page_shift;
     kp.sm_scale = p.sm_scale > 0.f ? p.sm_scale : 1.0f / sqrtf((float)d);
 
     auto all_zero = [](const int64_t s[3]) { return s[0] == 0 && s[1] == 0 && s[2] == 0; };

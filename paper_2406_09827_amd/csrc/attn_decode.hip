@@ -12,11 +12,11 @@
 
 namespace hipattn {
 
-template <int BK, int D>
+template <int BK, int D, int ROWS>
 __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 {
     constexpr int LPR = D / 8, RPW = 64 / LPR;
-    constexpr int U = 8 / BK;  // blocks per lane group and stage: 8 key + 8 value row loads per lane, two stages in flight
+    constexpr int U = ROWS / BK;  // blocks per lane group and stage: ROWS key + ROWS value row loads per lane, two stages in flight
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, lc = lane % LPR;
@@ -140,7 +140,13 @@ hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
     const int64_t waves = (int64_t)p.batch * p.hq;
     if (waves == 0) return hipSuccess;
     dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
-#define HIPATTN_LAUNCH(BKV, DV) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV>), grid, block, 0, st, p)
+    // deep stages when a wave is alone on its SIMD, shallow ones (more waves per SIMD) at large batch
+    const bool deep = waves < 4096;
+#define HIPATTN_LAUNCH(BKV, DV)                                                                        \
+    do {                                                                                               \
+        if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8>), grid, block, 0, st, p);         \
+        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4>), grid, block, 0, st, p);              \
+    } while (0)
     if (p.d == 64) {
         if (p.bk == 1) HIPATTN_LAUNCH(1, 64);
         else if (p.bk == 2) HIPATTN_LAUNCH(2, 64);

@@ -20,6 +20,7 @@ struct KParams {
     int64_t ks_b, ks_h, ks_r;
     int64_t os_b, os_h, os_r;
     int32_t batch, hq, hkv, g, d, q_len, max_kv_len, kb, bq, bk, nqb, page_size, max_pages;
+    int32_t page_shift;        // log2(page_size) when it is a power of two, else -1
     float sm_scale;
 };
 
@@ -56,8 +57,11 @@ __device__ __forceinline__ uint32_t score_key(float f)
 __device__ __forceinline__ int64_t kv_row_offset(const KParams &p, int b, int h, int t)
 {
     if (p.page_table) {
-        int pg = p.page_table[(int64_t)b * p.max_pages + t / p.page_size];
-        return (int64_t)pg * p.ks_b + (int64_t)h * p.ks_h + (int64_t)(t % p.page_size) * p.ks_r;
+        int pi, in_page;
+        if (p.page_shift >= 0) { pi = t >> p.page_shift; in_page = t & (p.page_size - 1); }
+        else { pi = t / p.page_size; in_page = t - pi * p.page_size; }
+        const int pg = p.page_table[(int64_t)b * p.max_pages + pi];
+        return (int64_t)pg * p.ks_b + (int64_t)h * p.ks_h + (int64_t)in_page * p.ks_r;
     }
     return (int64_t)b * p.ks_b + (int64_t)h * p.ks_h + (int64_t)t * p.ks_r;
 }

@@ -8,7 +8,7 @@
 // L1/L2 instead of going to HBM four times.
 //   * a key row is read by D/8 lanes, 16 bytes each (a full 128-bit coalesced row segment),
 //     multiplied with v_dot2_f32_bf16 and summed over the lanes with DPP adds;
-//   * two stages of 16 row loads per lane alternate, so up to 32 KB per wave are in flight
+//   * two stages of 16 (8 at large batch) row loads per lane alternate, so up to 32 KB per wave are in flight
 //     (a wave is alone on its SIMD at small batch, the memory pipeline has to be kept full
 //     from inside the wave);
 //   * scores -> per-wave LDS keys -> ordered threshold selection (once per wave, nothing
@@ -19,13 +19,13 @@
 
 namespace hipattn {
 
-template <int E, int BK, int D>
+template <int E, int BK, int D, int ROWS>
 __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
 {
     constexpr int NB = 64 * E;
     constexpr int LPR = D / 8;        // lanes per key row
     constexpr int RPW = 64 / LPR;     // rows (= branches) per wave-wide load
-    constexpr int U = 16 / BK;        // branches per lane group and stage: 16 row loads per lane, two stages in flight
+    constexpr int U = ROWS / BK;      // branches per lane group and stage: ROWS row loads per lane, two stages in flight
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
@@ -144,14 +144,25 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     for (int j = lane; j < kb; j += 64) out[j] = ns[j] * BK;
 }
 
+template <int BK, int D, int ROWS>
+static hipError_t launch_r(const KParams &p, dim3 grid, hipStream_t st)
+{
+    dim3 block(kThreads);
+    if (p.kb <= 128) hipLaunchKernelGGL((mask_decode_kernel<4, BK, D, ROWS>), grid, block, 0, st, p);
+    else if (p.kb <= 256) hipLaunchKernelGGL((mask_decode_kernel<8, BK, D, ROWS>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((mask_decode_kernel<16, BK, D, ROWS>), grid, block, 0, st, p);
+    return hipGetLastError();
+}
+
+// Few waves (small batch): each wave is alone on its SIMD and has to keep the memory pipeline
+// full by itself -> deep stages.  Many waves: shallower stages need fewer registers, so more
+// waves fit a SIMD and hide each other's latency (including the page-table lookups).
 template <int BK, int D>
 static hipError_t launch_e(const KParams &p, dim3 grid, hipStream_t st)
 {
-    dim3 block(kThreads);
-    if (p.kb <= 128) hipLaunchKernelGGL((mask_decode_kernel<4, BK, D>), grid, block, 0, st, p);
-    else if (p.kb <= 256) hipLaunchKernelGGL((mask_decode_kernel<8, BK, D>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((mask_decode_kernel<16, BK, D>), grid, block, 0, st, p);
-    return hipGetLastError();
+    const int64_t waves = (int64_t)p.batch * p.hq;
+    if (waves >= 4096) return launch_r<BK, D, 8>(p, grid, st);
+    return launch_r<BK, D, 16>(p, grid, st);
 }
 
 bool mask_decode_supported(const KParams &p, bool bf16)

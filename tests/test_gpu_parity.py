@@ -59,6 +59,15 @@ def test_decode_ragged_paged(flags, integer):
     U.run_case(w, flags)
 
 
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_decode_large_batch(integer):
+    # >= 4096 (sequence, head) problems selects the shallow-stage decode variant
+    w = synth.scaled(synth.C5, batch=128, kv_len=3000, ragged=(600, 3000), integer=integer)
+    rng = np.random.default_rng(2)
+    units = [(int(b), int(h), 0) for b, h in zip(rng.integers(0, 128, 300), rng.integers(0, 32, 300))]
+    U.run_case(w, 0, units=sorted(set(units)))
+
+
 @pytest.mark.parametrize("bk,d,k,hq,hkv", [(1, 128, 64, 4, 4), (4, 128, 1024, 8, 2), (2, 64, 256, 6, 2), (1, 64, 512, 4, 1),
                                           (4, 64, 2048, 2, 1)])
 def test_decode_variants(bk, d, k, hq, hkv):
