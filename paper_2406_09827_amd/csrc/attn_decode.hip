@@ -12,7 +12,7 @@
 
 namespace hipattn {
 
-template <int BK, int D, int ROWS>
+template <int BK, int D, int ROWS, bool PAGED>
 __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 {
     constexpr int LPR = D / 8, RPW = 64 / LPR;
@@ -38,6 +38,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
     // one stage = U blocks per lane group: BK key rows and BK value rows each, loaded
     // unconditionally (a block that does not count re-reads row 0 and gets probability 0).
     auto fetch = [&](int base, stage_t &kr, stage_t &vr, int (&first)[U]) __attribute__((always_inline)) {
+        int pg[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * RPW + grp;
@@ -45,7 +46,13 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
             if (j < kb) f = idx[j];
             if (f >= kv_len) f = -1;
             first[u] = f;
-            const int64_t off = kv_row_offset(p, b, hk, f >= 0 ? f : 0) + lc * 8;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) pg[u] = page_of_row<PAGED>(p, b, first[u] >= 0 ? first[u] : 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int f = first[u];
+            const int64_t off = row_offset_in<PAGED>(p, b, hk, f >= 0 ? f : 0, pg[u]) + lc * 8;
 #pragma unroll
             for (int n = 0; n < BK; ++n) {
                 const int dn = f >= 0 ? min(n, kv_len - 1 - f) : 0;
@@ -141,11 +148,13 @@ hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
     if (waves == 0) return hipSuccess;
     dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
     // deep stages when a wave is alone on its SIMD, shallow ones (more waves per SIMD) at large batch
-    const bool deep = waves < 4096;
+    const bool deep = waves < 4096, paged = p.page_table != nullptr;
 #define HIPATTN_LAUNCH(BKV, DV)                                                                        \
     do {                                                                                               \
-        if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8>), grid, block, 0, st, p);         \
-        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4>), grid, block, 0, st, p);              \
+        if (deep && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, true>), grid, block, 0, st, p);        \
+        else if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, false>), grid, block, 0, st, p);           \
+        else if (paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true>), grid, block, 0, st, p);           \
+        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false>), grid, block, 0, st, p);                     \
     } while (0)
     if (p.d == 64) {
         if (p.bk == 1) HIPATTN_LAUNCH(1, 64);

@@ -31,7 +31,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-template <int D>
+template <int D, bool PAGED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
 {
     constexpr int KS = D / 16;     // k-steps of S^T = K Q^T
@@ -118,9 +118,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             const int t = first + (ki & (bk - 1));
             if (first >= 0 && first < kv_len && t < kv_len) t_c = t;
         }
-        if (hh == 0) {
-            tk[col] = t_c;
-            mo[col] = (uint32_t)(kv_row_offset(p, b, hk, t_c >= 0 ? t_c : 0) >> 3);
+        {
+            const int tr = t_c >= 0 ? t_c : 0;
+            const int64_t eo = row_offset_in<PAGED>(p, b, hk, tr, page_of_row<PAGED>(p, b, tr));
+            if (hh == 0) {
+                tk[col] = t_c;
+                mo[col] = (uint32_t)(eo >> 3);
+            }
         }
         const int flags = (__ballot(t_c >= 0 && t_c <= pos0 + n_rows - 1) != 0 ? 1 : 0) |
                           (__ballot(t_c < 0 || t_c > pos0) != 0 ? 2 : 0);
@@ -283,8 +287,14 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     const int64_t waves = groups * per_group;
     if (waves == 0) return hipSuccess;
     dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
-    if (p.d == 64) hipLaunchKernelGGL((attn_mfma_kernel<64>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-    else hipLaunchKernelGGL((attn_mfma_kernel<128>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+    const bool paged = p.page_table != nullptr;
+    if (p.d == 64) {
+        if (paged) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else hipLaunchKernelGGL((attn_mfma_kernel<64, false>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+    } else {
+        if (paged) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else hipLaunchKernelGGL((attn_mfma_kernel<128, false>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+    }
     return hipGetLastError();
 }
 

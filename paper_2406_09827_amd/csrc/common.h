@@ -66,6 +66,22 @@ __device__ __forceinline__ int64_t kv_row_offset(const KParams &p, int b, int h,
     return (int64_t)b * p.ks_b + (int64_t)h * p.ks_h + (int64_t)t * p.ks_r;
 }
 
+// The same in two steps, for kernels that want all page-table reads of a batch of rows in
+// flight before the first dependent row load is issued (a dependent load in the middle of a
+// batch makes the wave wait for every older load as well).
+template <bool PAGED> __device__ __forceinline__ int page_of_row(const KParams &p, int b, int t)
+{
+    if (!PAGED) return 0;
+    const int pi = p.page_shift >= 0 ? (t >> p.page_shift) : (t / p.page_size);
+    return p.page_table[(int64_t)b * p.max_pages + pi];
+}
+template <bool PAGED> __device__ __forceinline__ int64_t row_offset_in(const KParams &p, int b, int h, int t, int page)
+{
+    if (!PAGED) return (int64_t)b * p.ks_b + (int64_t)h * p.ks_h + (int64_t)t * p.ks_r;
+    const int in_page = p.page_shift >= 0 ? (t & (p.page_size - 1)) : (t % p.page_size);
+    return (int64_t)page * p.ks_b + (int64_t)h * p.ks_h + (int64_t)in_page * p.ks_r;
+}
+
 __device__ __forceinline__ int lane_prefix_count(uint64_t mask)
 {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));

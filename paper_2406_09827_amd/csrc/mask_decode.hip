@@ -19,7 +19,7 @@
 
 namespace hipattn {
 
-template <int E, int BK, int D, int ROWS>
+template <int E, int BK, int D, int ROWS, bool PAGED>
 __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
 {
     constexpr int NB = 64 * E;
@@ -65,6 +65,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
         // one stage = U branches per lane group: node lookup, then the (unconditional) loads of
         // the representative block's BK rows.  t0 < 0 marks an empty branch.
         auto fetch = [&](int base, stage_t &kv, int (&t0)[U]) __attribute__((always_inline)) {
+            int pg[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int slot = base + u * RPW + grp, node = slot >> 1;
@@ -78,11 +79,16 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
                     t = (bs + ((be - bs) >> 1)) * BK;
                 }
                 t0[u] = ok ? t : -1;
-                const bf16_t *src = Kbase + kv_row_offset(p, b, hk, ok ? t : 0) + lc * 8;
+                pg[u] = page_of_row<PAGED>(p, b, ok ? t : 0);  // all page lookups of the stage first
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0[u] >= 0 ? t0[u] : 0;
+                const bf16_t *src = Kbase + row_offset_in<PAGED>(p, b, hk, t, pg[u]) + lc * 8;
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
                     // rows past the end of the sequence re-read its last row and are ignored below
-                    const int dn = ok ? min(n, kv_len - 1 - t) : 0;
+                    const int dn = t0[u] >= 0 ? min(n, kv_len - 1 - t) : 0;
                     const uint4 x = *(const uint4 *)(src + (int64_t)dn * p.ks_r);
                     const int q4 = 4 * (u * BK + n);
                     kv[q4] = x.x; kv[q4 + 1] = x.y; kv[q4 + 2] = x.z; kv[q4 + 3] = x.w;
@@ -148,9 +154,15 @@ template <int BK, int D, int ROWS>
 static hipError_t launch_r(const KParams &p, dim3 grid, hipStream_t st)
 {
     dim3 block(kThreads);
-    if (p.kb <= 128) hipLaunchKernelGGL((mask_decode_kernel<4, BK, D, ROWS>), grid, block, 0, st, p);
-    else if (p.kb <= 256) hipLaunchKernelGGL((mask_decode_kernel<8, BK, D, ROWS>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((mask_decode_kernel<16, BK, D, ROWS>), grid, block, 0, st, p);
+#define HIPATTN_LAUNCH(EV)                                                                                  \
+    do {                                                                                                    \
+        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true>), grid, block, 0, st, p);  \
+        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false>), grid, block, 0, st, p);       \
+    } while (0)
+    if (p.kb <= 128) HIPATTN_LAUNCH(4);
+    else if (p.kb <= 256) HIPATTN_LAUNCH(8);
+    else HIPATTN_LAUNCH(16);
+#undef HIPATTN_LAUNCH
     return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@ __device__ __forceinline__ float max_half_swap(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-template <int MT, int E, int D>
+template <int MT, int E, int D, bool PAGED>
 __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_bk, int xcd_map)
 {
     constexpr int NB = 64 * E;  // branch slots
@@ -146,7 +146,11 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             t = row_ok ? tt : -1;
             slot = slot_ok ? sl : ~sl;
             // row offset in 16-byte units (strides are multiples of 8 elements)
-            if (hh == 0) meta[col] = (uint32_t)(kv_row_offset(p, b, hk, row_ok ? tt : 0) >> 3);
+            {
+                const int tr = row_ok ? tt : 0;
+                const int64_t eo = row_offset_in<PAGED>(p, b, hk, tr, page_of_row<PAGED>(p, b, tr));
+                if (hh == 0) meta[col] = (uint32_t)(eo >> 3);
+            }
             wave_lds_sync();
             uint32_t off[NLD];
 #pragma unroll
@@ -266,9 +270,17 @@ template <int MT, int D>
 static hipError_t launch_e(const KParams &p, int log_bk, int xcd_map, dim3 grid, hipStream_t st)
 {
     dim3 block(kThreads);
-    if (p.kb <= 128) hipLaunchKernelGGL((mask_mfma_kernel<MT, 4, D>), grid, block, 0, st, p, log_bk, xcd_map);
-    else if (p.kb <= 256) hipLaunchKernelGGL((mask_mfma_kernel<MT, 8, D>), grid, block, 0, st, p, log_bk, xcd_map);
-    else hipLaunchKernelGGL((mask_mfma_kernel<MT, 16, D>), grid, block, 0, st, p, log_bk, xcd_map);
+    // the page-table variant is a separate instantiation: a table read in the row-offset code
+    // would otherwise put a full memory wait into the contiguous path's load pipeline
+#define HIPATTN_LAUNCH(EV)                                                                                           \
+    do {                                                                                                             \
+        if (p.page_table) hipLaunchKernelGGL((mask_mfma_kernel<MT, EV, D, true>), grid, block, 0, st, p, log_bk, xcd_map);  \
+        else hipLaunchKernelGGL((mask_mfma_kernel<MT, EV, D, false>), grid, block, 0, st, p, log_bk, xcd_map);       \
+    } while (0)
+    if (p.kb <= 128) HIPATTN_LAUNCH(4);
+    else if (p.kb <= 256) HIPATTN_LAUNCH(8);
+    else HIPATTN_LAUNCH(16);
+#undef HIPATTN_LAUNCH
     return hipGetLastError();
 }
 

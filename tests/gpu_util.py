@@ -23,8 +23,8 @@ def host(x):
 
 
 def _max_len(w, x):
-    # with a page table the bound is what the table can address
-    return None if x["page_table"] is not None else w.kv_len
+    # ragged + paged: the bound is what the table can address; otherwise the exact length
+    return None if (x["page_table"] is not None and x["kv_lens"] is not None) else w.kv_len
 
 
 def gpu_mask(w, x, flags=0):

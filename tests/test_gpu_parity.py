@@ -59,6 +59,17 @@ def test_decode_ragged_paged(flags, integer):
     U.run_case(w, flags)
 
 
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_prefill_paged(flags, integer):
+    # causal prefill over a paged KV pool (16-token pages, random page table), two sequences
+    w = synth.scaled(synth.C2, batch=2, q_len=3000, kv_len=3000, n_q_heads=4, n_kv_heads=2, k=256, spike_every=512,
+                     page_size=16, integer=integer)
+    nqb = w.n_query_blocks
+    units = [(b, h, qb) for b in range(2) for h in range(4) for qb in (0, 3, 4, 5, 20, 50, nqb - 2, nqb - 1)]
+    U.run_case(w, flags, units=units)
+
+
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_decode_large_batch(integer):
     # >= 4096 (sequence, head) problems selects the shallow-stage decode variant
