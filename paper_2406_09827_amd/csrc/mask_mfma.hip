@@ -17,7 +17,9 @@
 //     the max over the admissible query rows (in-lane, then lanes l and l+32) and over the
 //     bk keys of the block (neighbouring lanes, DPP).
 //   * Scores go to the wave's LDS slice as order-preserving integer keys; the wave runs the
-//     ordered threshold selection and writes the surviving nodes into its second node list.
+//     ordered threshold selection, compacts the surviving nodes in place and writes, per
+//     surviving node, the representative blocks of its two branches into a branch table, so
+//     the scoring loop of the next round does one table lookup per key row.
 // Node ranges are block indices [s, e); the list stays sorted by position throughout, which
 // is why the result needs no sort.
 #include "common.h"
@@ -42,7 +44,8 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
     constexpr int NB = 64 * E;  // branch slots
     constexpr int KS = D / 16;  // MFMA k-steps per key row
     __shared__ uint32_t keys_s[4][NB];
-    __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
+    __shared__ int nds[4][NB / 2], nde[4][NB / 2];  // node ranges [s, e) in key blocks
+    __shared__ int brt_s[4][NB];                    // per branch slot: first key of its centre block, -1 = empty
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
     __shared__ __attribute__((aligned(16))) uint32_t meta_s[4][32];
 
@@ -106,14 +109,26 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
     constexpr int ROWB = D * 2;    // bytes per row
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * NLD)));
     uint32_t *keys = keys_s[wave];
+    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave];
     char *tile_s = (char *)tile_buf[wave];
     uint32_t *meta = meta_s[wave];
-    for (int i = lane; i < NB; i += 64) keys[i] = 0;
+
+    // the two branches of node [s, e): left [s, mid) (empty for a one-block node), right [mid, e);
+    // each is represented by its centre block.  Written once per surviving node, so the
+    // scoring loop only looks the representative up.
+    auto put_branches = [&](int j, int s, int e) __attribute__((always_inline)) {
+        const int mid = s + ((e - s) >> 1);
+        brt[2 * j] = mid > s ? (s + ((mid - s) >> 1)) << log_bk : -1;
+        brt[2 * j + 1] = (mid + ((e - mid) >> 1)) << log_bk;
+    };
+    for (int i = lane; i < NB; i += 64) { keys[i] = 0; brt[i] = -1; }
+    wave_lds_sync();
     {
         const int a = Tb / kb, r = Tb % kb;
         for (int j = lane; j < kb; j += 64) {
-            nds[wave][0][j] = chunk_bound(j, a, r, kb);
-            nde[wave][0][j] = chunk_bound(j + 1, a, r, kb);
+            const int s = chunk_bound(j, a, r, kb), e = chunk_bound(j + 1, a, r, kb);
+            ns[j] = s; ne[j] = e;
+            put_branches(j, s, e);
         }
     }
     wave_lds_sync();
@@ -122,35 +137,29 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
     const int n_tiles = (2 * kb * bk + 31) >> 5;
     const bool full_rows = n_rows == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
-    int cur = 0;
+    // byte offset of row 0 of this sequence / kv head (contiguous layout only)
+    const char *Kseq = (const char *)(Kbase + (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h);
+    const uint32_t row_bytes = (uint32_t)p.ks_r * 2u;
 
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
-        const int *ns = nds[wave][cur], *ne = nde[wave][cur];
 
         // Row metadata of one tile (lane = row col) and the coalesced loads of its 32 rows.
         // t = key position of this lane's row, or -1 if the row does not count;
         // slot = branch slot, complemented when the branch is empty.
         auto fetch = [&](int tile, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
             const int rr = tile * 32 + col;
-            const int sl = rr >> log_bk, node = sl >> 1;
-            bool slot_ok = node < kb;
-            int tt = 0;
-            if (slot_ok) {
-                const int s = ns[node], e = ne[node];
-                const int mid = s + ((e - s) >> 1);
-                const int bs = (sl & 1) ? mid : s, be = (sl & 1) ? e : mid;
-                slot_ok = be > bs;
-                tt = ((bs + ((be - bs) >> 1)) << log_bk) + (rr & (bk - 1));
-            }
-            const bool row_ok = slot_ok && tt < kv_len;
+            const int sl = rr >> log_bk;
+            const int tf = sl < NB ? brt[sl] : -1;
+            const int tt = tf + (rr & (bk - 1));
+            const bool row_ok = tf >= 0 && tt < kv_len;
             t = row_ok ? tt : -1;
-            slot = slot_ok ? sl : ~sl;
-            // row offset in 16-byte units (strides are multiples of 8 elements)
-            {
-                const int tr = row_ok ? tt : 0;
-                const int64_t eo = row_offset_in<PAGED>(p, b, hk, tr, page_of_row<PAGED>(p, b, tr));
-                if (hh == 0) meta[col] = (uint32_t)(eo >> 3);
-            }
+            slot = tf >= 0 ? sl : ~sl;
+            const int tr = row_ok ? tt : 0;
+            // row offset: bytes from the sequence start (contiguous), or 16-byte units from the pool start
+            uint32_t mo;
+            if (PAGED) mo = (uint32_t)(row_offset_in<true>(p, b, hk, tr, page_of_row<true>(p, b, tr)) >> 3);
+            else mo = (uint32_t)tr * row_bytes;
+            if (hh == 0) meta[col] = mo;
             wave_lds_sync();
             uint32_t off[NLD];
 #pragma unroll
@@ -161,7 +170,9 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
             wave_lds_sync();
 #pragma unroll
             for (int j = 0; j < NLD; ++j) {
-                const uint4 x = *(const uint4 *)(Kbase + ((int64_t)off[j] << 3) + lc * 8);
+                uint4 x;
+                if (PAGED) x = *(const uint4 *)(Kbase + ((int64_t)off[j] << 3) + lc * 8);
+                else x = *(const uint4 *)(Kseq + (off[j] + (uint32_t)lc * 16u));
                 R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
             }
         };
@@ -240,29 +251,38 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel(KParams p, int log_
         }
         wave_lds_sync();
 
-        // ordered top-kb selection into this wave's other node list
+        // ordered top-kb selection; survivors are compacted in place: every lane first reads the
+        // parents of the slots it keeps, then (after all reads) writes the new nodes and their branches
         uint32_t key[E];
         bool keep[E];
         int dest[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
         select_topk_ordered<E>(key, kb, keep, dest);
-        int *ns2 = nds[wave][cur ^ 1], *ne2 = nde[wave][cur ^ 1];
+        int cs[E], ce[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) {
+            cs[i] = 0; ce[i] = 0;
             if (keep[i]) {
                 const int slot = i * 64 + lane, node = slot >> 1;
                 const int s = ns[node], e = ne[node];
                 const int mid = s + ((e - s) >> 1);
-                ns2[dest[i]] = (slot & 1) ? mid : s;
-                ne2[dest[i]] = (slot & 1) ? e : mid;
+                cs[i] = (slot & 1) ? mid : s;
+                ce[i] = (slot & 1) ? e : mid;
             }
         }
-        cur ^= 1;
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            if (keep[i]) {
+                ns[dest[i]] = cs[i];
+                ne[dest[i]] = ce[i];
+                put_branches(dest[i], cs[i], ce[i]);
+            }
+        }
         wave_lds_sync();
     }
 
-    const int *ns = nds[wave][cur];
     for (int j = lane; j < kb; j += 64) out[j] = ns[j] << log_bk;
 }
 
@@ -286,8 +306,10 @@ static hipError_t launch_e(const KParams &p, int log_bk, int xcd_map, dim3 grid,
 
 bool mask_mfma_supported(const KParams &p, bool bf16)
 {
-    // k/bk above 512 would need more than the 64 KB of statically allocated LDS: generic kernel
-    return bf16 && p.q_len > 1 && p.bk <= 16 && (p.bk & (p.bk - 1)) == 0 && p.bq <= 64 && p.kb <= 512;
+    // k/bk above 512: generic kernel.  The contiguous variant addresses key rows by 32-bit byte
+    // offsets from the start of a (sequence, kv head) slice.
+    const bool fits32 = p.page_table || (int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31);
+    return bf16 && p.q_len > 1 && p.bk <= 16 && (p.bk & (p.bk - 1)) == 0 && p.bq <= 64 && p.kb <= 512 && fits32;
 }
 
 hipError_t launch_mask_mfma(const KParams &p, hipStream_t st)
