@@ -11,7 +11,9 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhipattn.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+# -fno-honor-nans: max/min compile to single instructions (no NaN quieting); infinities are
+# still honoured (the kernels use -inf as "no score").  NaN inputs are outside the contract.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

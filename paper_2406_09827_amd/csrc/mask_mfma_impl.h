@@ -1,0 +1,377 @@
+// Hierarchical mask estimation for bf16 prefill on CDNA4 matrix cores
+// (paper Alg. 1; the block approximation of Sec. 3.2 is what makes the branch scoring a
+// dense query-block x gathered-key-rows contraction).
+//
+// Work item = one WAVE = one (sequence, query head, query block); four independent work
+// items per workgroup, no workgroup barrier and no work done twice.
+//   * The query block (<= 64 rows) sits in registers as the MFMA A operand.
+//   * A round scores 2*kb branches = 2*kb*bk gathered key rows in tiles of 32 rows.  The rows
+//     are loaded COALESCED (a row = D/8 consecutive lanes x 16 bytes, so the address unit sees
+//     whole cache lines instead of 64 separate ones), parked in two alternating register sets
+//     while in flight (two tiles ahead), written into the wave's LDS tile with an XOR swizzle
+//     and read back in the MFMA B-operand layout (lane l: row l % 32, 16-byte chunk l / 32 of
+//     each 32-byte step) without bank conflicts.  A loading lane finds the rows it loads with
+//     ONE read of the branch table (its rows belong to consecutive branch slots), issued a
+//     further tile ahead, so no LDS round trip sits between two tiles.  Rows of empty
+//     branches load row 0 of the sequence (always mapped) and drop the result: loads stay
+//     unconditional.
+//   * v_mfma_f32_32x32x16_bf16 gives a 32(query) x 32(key) score tile; the branch score is
+//     the max over the admissible query rows (in-lane, then lanes l and l+32) and over the
+//     bk keys of the block (neighbouring lanes, DPP).
+//   * Scores go to the wave's LDS slice as order-preserving integer keys; the wave runs the
+//     ordered threshold selection, compacts the surviving nodes in place and writes, per
+//     surviving node, the representative blocks of its two branches into a branch table, so
+//     the scoring loop of the next round does one table lookup per key row.
+// Node ranges are block indices [s, e); the list stays sorted by position throughout, which
+// is why the result needs no sort.
+#pragma once
+#include "common.h"
+#include "launch.h"
+
+namespace hipattn {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// max over lanes l and l ^ 32 (both get it)
+__device__ __forceinline__ float max_half_swap(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// MT = 32-row query tiles (1 or 2), E = branch slots / 64, D = head dim, LB = log2(bk)
+template <int MT, int E, int D, bool PAGED, int LB>
+__device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
+{
+    constexpr int NB = 64 * E;     // branch slots
+    constexpr int KS = D / 16;     // MFMA k-steps per key row
+    constexpr int BK = 1 << LB;
+    constexpr int CPR = D / 8;     // 16-byte chunks per key row
+    constexpr int RPI = 64 / CPR;  // rows per wave-wide load
+    constexpr int NLD = 32 / RPI;  // rows (= loads) per lane and tile
+    constexpr int SPL = NLD >> LB; // branch slots a loading lane's rows belong to (>= 1)
+    constexpr int ROWB = D * 2;    // bytes per row
+    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * NLD)));
+    static_assert(SPL >= 1, "bk too large for this kernel");
+    __shared__ uint32_t keys_s[4][NB];
+    __shared__ int nds[4][NB / 2], nde[4][NB / 2];                   // node ranges [s, e) in key blocks
+    __shared__ __attribute__((aligned(16))) int brt_s[4][NB];        // per branch slot: first key of its centre block, -1 = empty
+    __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, hh = lane >> 5;
+
+    // ---- which (sequence, head, query block) this wave owns.  With `xcd_map` the workgroups an
+    // XCD receives (blockIdx.x % 8) all read the same KV head; query blocks go from the longest
+    // prefix down, the query heads of a KV group are adjacent.
+    const int64_t groups = (int64_t)p.batch * p.hkv;
+    const int64_t per_group = (int64_t)p.g * p.nqb;
+    int64_t group, o;
+    if (xcd_map) {
+        const int64_t bid = blockIdx.x;
+        const int64_t seq = (bid >> 3) * 4 + wave;
+        group = (bid & 7) + 8 * (seq / per_group);
+        o = seq % per_group;
+    } else {
+        const int64_t lin = (int64_t)blockIdx.x * 4 + wave;
+        group = lin / per_group;
+        o = lin % per_group;
+    }
+    if (group >= groups) return;
+    const int qb = p.nqb - 1 - (int)(o / p.g);
+    const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
+    const int h = hk * p.g + (int)(o % p.g);
+    const int kb = p.kb;
+
+    const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
+    const int row0 = qb * p.bq;
+    const int n_rows = min(p.bq, p.q_len - row0);
+    const int pos0 = kv_len - p.q_len + row0;
+    const int L = min(kv_len, pos0 + n_rows);
+    int32_t *out = p.idx_out + (((int64_t)b * p.hq + h) * p.nqb + qb) * kb;
+
+    const int Tb = L > 0 ? (L + BK - 1) >> LB : 0;
+    if (Tb <= kb) {
+        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j << LB : kSentinel;
+        return;
+    }
+
+    // query block as MFMA A operand: lane holds row (lane % 32) [+32], 8 channels per k-step
+    bf16x8 qf[MT][KS];
+    {
+        const bf16_t *Qb = (const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + (int64_t)row0 * p.qs_r;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int i = mt * 32 + col;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (i < n_rows) v = *(const uint4 *)(Qb + (int64_t)i * p.qs_r + kk * 16 + hh * 8);
+                qf[mt][kk] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+    }
+
+    uint32_t *keys = keys_s[wave];
+    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave];
+    char *tile_s = (char *)tile_buf[wave];
+
+    // the two branches of node [s, e): left [s, mid) (empty for a one-block node), right [mid, e);
+    // each is represented by its centre block.  Written once per surviving node, so the
+    // scoring loop only looks the representative up.
+    auto put_branches = [&](int j, int s, int e) __attribute__((always_inline)) {
+        const int mid = s + ((e - s) >> 1);
+        brt[2 * j] = mid > s ? (s + ((mid - s) >> 1)) << LB : -1;
+        brt[2 * j + 1] = (mid + ((e - mid) >> 1)) << LB;
+    };
+    for (int i = lane; i < NB; i += 64) { keys[i] = 0; brt[i] = -1; }
+    wave_lds_sync();
+    {
+        const int a = Tb / kb, r = Tb % kb;
+        for (int j = lane; j < kb; j += 64) {
+            const int s = chunk_bound(j, a, r, kb), e = chunk_bound(j + 1, a, r, kb);
+            ns[j] = s; ne[j] = e;
+            put_branches(j, s, e);
+        }
+    }
+    wave_lds_sync();
+
+    const bf16_t *Kbase = (const bf16_t *)p.K;
+    const int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
+    const bool full_rows = n_rows == 32 * MT;
+    const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
+    // row 0 of this sequence / kv head (contiguous layout only)
+    const char *Kseq = (const char *)(Kbase + (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h);
+    const uint32_t row_bytes = (uint32_t)p.ks_r * 2u;
+
+    // Branch-table entries one tile needs: m[0..SPL-1] for the rows this lane LOADS, m[SPL] for
+    // the row it SCORES (row col of the tile).
+    struct meta_t { int m[SPL + 1]; };
+    auto read_meta = [&](int tile, meta_t &mt_) __attribute__((always_inline)) {
+        const int *src = brt + tile * (32 >> LB) + lg * SPL;
+        if (SPL == 1) mt_.m[0] = src[0];
+        else if (SPL == 2) { const int2 v = *(const int2 *)src; mt_.m[0] = v.x; mt_.m[1] = v.y; }
+        else {
+#pragma unroll
+            for (int i = 0; i < SPL; i += 4) {
+                const int4 v = *(const int4 *)(src + i);
+                mt_.m[i] = v.x; mt_.m[i + 1] = v.y; mt_.m[i + 2] = v.z; mt_.m[i + 3] = v.w;
+            }
+        }
+        mt_.m[SPL] = brt[(tile * 32 + col) >> LB];
+    };
+
+    // Coalesced loads of a tile's 32 rows from the metadata read earlier.
+    // t = key position of this lane's scored row, or -1 if the row does not count;
+    // slot = its branch slot, complemented when the branch is empty.
+    auto load_rows = [&](int tile, const meta_t &mt_, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
+        {
+            const int sl = (tile * 32 + col) >> LB, tf = mt_.m[SPL];
+            const int tt = tf + (col & (BK - 1));
+            t = (tf >= 0 && tt < kv_len) ? tt : -1;
+            slot = tf >= 0 ? sl : ~sl;
+        }
+        // per branch slot: offset of the block's first row; rows past the end of the sequence
+        // re-read its last row (their score is dropped: t < 0 above)
+        const int last = kv_len - 1;
+#pragma unroll
+        for (int i = 0; i < SPL; ++i) {
+            const int tf = max(mt_.m[i], 0);
+            if (PAGED) {
+                // a block never straddles a page
+                const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
+#pragma unroll
+                for (int n = 0; n < BK; ++n) {
+                    const uint4 x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + n, last) - tf) * p.ks_r);
+                    const int j = i * BK + n;
+                    R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
+                }
+            } else {
+#pragma unroll
+                for (int n = 0; n < BK; ++n) {
+                    const uint4 x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + n, last) * row_bytes + (uint32_t)lc * 16u));
+                    const int j = i * BK + n;
+                    R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
+                }
+            }
+        }
+    };
+
+    // registers -> swizzled LDS tile: row r = lg*NLD + j, chunk lc goes to slot lc ^ (r % CPR)
+    auto park = [&](const stage_t &R) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const int r = lg * NLD + j;
+            *(uint4 *)(tile_s + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) =
+                make_uint4(R[4 * j], R[4 * j + 1], R[4 * j + 2], R[4 * j + 3]);
+        }
+    };
+
+    auto score = [&](int t, int slot) __attribute__((always_inline)) {
+        f32x16 acc[MT];
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+        // all operand reads first (one LDS latency per tile, not one per k-step), then the multiplies
+        uint4 kv[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+            kv[kk] = *(const uint4 *)(tile_s + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
+        __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from re-interleaving reads and multiplies
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv[kk]), acc[mt], 0, 0, 0);
+        // max over the admissible query rows of this lane's key column
+        const int lo = t - pos0;  // rows i < lo would look into the future
+        float v = -INFINITY;
+        if (full_rows && __ballot(lo > 0) == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float w[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) w[g] = fmaxf(fmaxf(acc[mt][4 * g], acc[mt][4 * g + 1]), fmaxf(acc[mt][4 * g + 2], acc[mt][4 * g + 3]));
+                v = fmaxf(v, fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])));
+            }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = mt * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+                    if (i >= lo && i < n_rows) v = fmaxf(v, acc[mt][r]);
+                }
+        }
+        if (t < 0) v = -INFINITY;
+        v = max_half_swap(v);
+        if (LB >= 1) v = fmaxf(v, dpp_f<0xB1>(v));  // lane ^ 1
+        if (LB >= 2) v = fmaxf(v, dpp_f<0x4E>(v));  // lane ^ 2
+        const int sl = slot < 0 ? ~slot : slot;
+        if (hh == 0 && (col & (BK - 1)) == 0) keys[sl] = slot < 0 ? 0u : score_key(v);
+    };
+
+    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
+        // pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two
+        stage_t R0, R1;  // one vector value each, so the staged rows stay in registers
+        meta_t m0, m1;
+        int t0 = -1, s0 = ~0, t1 = -1, s1 = ~0;
+        read_meta(0, m0);
+        if (n_tiles > 1) read_meta(1, m1);
+        load_rows(0, m0, R0, t0, s0);
+        if (n_tiles > 2) read_meta(2, m0);
+        if (n_tiles > 1) {
+            load_rows(1, m1, R1, t1, s1);
+            if (n_tiles > 3) read_meta(3, m1);
+        }
+        for (int tile = 0; tile < n_tiles; tile += 2) {
+            {
+                const int tc = t0, sc = s0;
+                park(R0);
+                if (tile + 2 < n_tiles) {
+                    load_rows(tile + 2, m0, R0, t0, s0);
+                    if (tile + 4 < n_tiles) read_meta(tile + 4, m0);
+                }
+                wave_lds_sync();
+                score(tc, sc);
+                wave_lds_sync();
+            }
+            if (tile + 1 < n_tiles) {
+                const int tc = t1, sc = s1;
+                park(R1);
+                if (tile + 3 < n_tiles) {
+                    load_rows(tile + 3, m1, R1, t1, s1);
+                    if (tile + 5 < n_tiles) read_meta(tile + 5, m1);
+                }
+                wave_lds_sync();
+                score(tc, sc);
+                wave_lds_sync();
+            }
+        }
+
+        // ordered top-kb selection; survivors are compacted in place: every lane first reads the
+        // parents of the slots it keeps, then (after all reads) writes the new nodes and their branches
+        uint32_t key[E];
+        bool keep[E];
+        int dest[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
+        select_topk_ordered<E>(key, kb, keep, dest);
+        int cs[E], ce[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            cs[i] = 0; ce[i] = 0;
+            if (keep[i]) {
+                const int slot = i * 64 + lane, node = slot >> 1;
+                const int s = ns[node], e = ne[node];
+                const int mid = s + ((e - s) >> 1);
+                cs[i] = (slot & 1) ? mid : s;
+                ce[i] = (slot & 1) ? e : mid;
+            }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < E; ++i) {
+            if (keep[i]) {
+                ns[dest[i]] = cs[i];
+                ne[dest[i]] = ce[i];
+                put_branches(dest[i], cs[i], ce[i]);
+            }
+        }
+        wave_lds_sync();
+    }
+
+    for (int j = lane; j < kb; j += 64) out[j] = ns[j] << LB;
+}
+
+// One query tile: two waves per SIMD (register budget 256); two query tiles: one wave per SIMD.
+template <int E, int D, bool PAGED, int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void mask_mfma_kernel_q32(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, E, D, PAGED, LB>(p, xcd_map);
+}
+template <int E, int D, bool PAGED, int LB>
+__global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int xcd_map)
+{
+    mask_mfma_body<2, E, D, PAGED, LB>(p, xcd_map);
+}
+
+template <int MT, int D, int LB>
+static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, hipStream_t st)
+{
+    dim3 block(kThreads);
+    // the page-table variant is a separate instantiation: a table read in the row-offset code
+    // would otherwise put a full memory wait into the contiguous path's load pipeline
+#define HIPATTN_LAUNCH(EV)                                                                                          \
+    do {                                                                                                            \
+        if (MT == 1) {                                                                                              \
+            if (p.page_table) hipLaunchKernelGGL((mask_mfma_kernel_q32<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);   \
+            else hipLaunchKernelGGL((mask_mfma_kernel_q32<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);      \
+        } else {                                                                                                    \
+            if (p.page_table) hipLaunchKernelGGL((mask_mfma_kernel_q64<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);   \
+            else hipLaunchKernelGGL((mask_mfma_kernel_q64<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);      \
+        }                                                                                                           \
+    } while (0)
+    if (p.kb <= 256) HIPATTN_LAUNCH(8);
+    else HIPATTN_LAUNCH(16);
+#undef HIPATTN_LAUNCH
+    return hipGetLastError();
+}
+
+// One translation unit per key-block size instantiates this.
+template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t st)
+{
+    const int64_t groups = (int64_t)p.batch * p.hkv;
+    const int64_t per_group = (int64_t)p.g * p.nqb;
+    const int xcd_map = (groups % 8 == 0 && per_group % 4 == 0) ? 1 : 0;
+    const int64_t units = groups * per_group;
+    if (units == 0) return hipSuccess;
+    dim3 grid((unsigned)((units + 3) / 4));
+    if (p.bq <= 32) return p.d == 64 ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st);
+    return p.d == 64 ? launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, st);
+}
+
+}  // namespace hipattn
