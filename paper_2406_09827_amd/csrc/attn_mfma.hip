@@ -10,9 +10,10 @@
 //                          The result has one query per lane and 16 keys in its registers,
 //                          so the softmax statistics of a query are lane-local (plus one
 //                          exchange with lane ^ 32) and P^T is already in B-operand layout.
-//   O^T += V_tile^T . P^T  (P as hi + lo bf16 terms) the value rows are loaded coalesced, staged in this wave's LDS
-//                          slice and read back channel-major (the contraction runs over
-//                          keys, so V has to be transposed on the way to the A operand).
+//   O^T += V_tile^T . P^T  (P as hi + lo bf16 terms) the value rows are loaded coalesced, staged
+//                          in this wave's LDS slice and read back channel-major with the LDS
+//                          transpose read ds_read_b64_tr_b16 (the contraction runs over keys, so
+//                          V has to be transposed on the way to the A operand).
 // The key positions of a tile and their row offsets are published through a small per-wave
 // LDS array so that every lane can mask by (key position, query position).
 #include "common.h"
@@ -24,6 +25,8 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 {
     constexpr int KS = D / 16;     // k-steps of S^T = K Q^T
     constexpr int CT = D / 32;     // 32-channel tiles of O^T
-    constexpr int PITCH = D + 8;   // value tile row pitch in bf16: 16 bytes of padding per row
+    constexpr int PITCH = D + 32;  // value tile row pitch in bf16: 64 bytes of padding per row (4 keys x 2 channel halves fill the 64 banks)
     constexpr int CPR = D / 8;     // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;  // rows covered by one wave-wide 16-byte load
     constexpr int NLD = 32 / RPI;  // such loads per 32-row tile
@@ -228,22 +231,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 pl[st] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
             }
 
-            // ---- O^T += V^T P^T: value tile read back channel-major
+            // ---- O^T += V^T P^T: value tile read back channel-major with the LDS transpose read.
+            // ds_read_b64_tr_b16 works on blocks of 16 lanes: lanes 4e .. 4e+3 of a block point at 16
+            // consecutive bf16 of source row e (e = 0..3), and lane i of the block receives element i
+            // of each of the four rows.  Block = (channel half cb, key half hh): rows are 4 consecutive
+            // keys, so a lane ends up with 4 keys of its channel - half an A operand per read.
+            {
+                const int i16 = lane & 15, cb = (lane >> 4) & 1;
+                const bf16_t *src0 = vt + (4 * hh + (i16 >> 2)) * PITCH + cb * 16 + (i16 & 3) * 4;
 #pragma unroll
-            for (int st = 0; st < 2; ++st) {
+                for (int st = 0; st < 2; ++st) {
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    // A operand: channel ct*32 + col, keys (2st + e/4)*8 + 4hh + e%4, e = 0..7
-                    const bf16_t *src = vt + ((2 * st) * 8 + 4 * hh) * PITCH + ct * 32 + col;
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e2 = 0; e2 < 4; ++e2) {
-                        const int k0 = ((2 * e2) >> 2) * 8 + ((2 * e2) & 3);
-                        w[e2] = (uint32_t)src[k0 * PITCH] | ((uint32_t)src[(k0 + 1) * PITCH] << 16);
+                    for (int ct = 0; ct < CT; ++ct) {
+                        // keys 16st + 4hh + {0..3} and 16st + 8 + 4hh + {0..3}, channel ct*32 + col
+                        const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src0 + (16 * st) * PITCH + ct * 32));
+                        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src0 + (16 * st + 8) * PITCH + ct * 32));
+                        const uint2 a = __builtin_bit_cast(uint2, lo4), c2 = __builtin_bit_cast(uint2, hi4);
+                        const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, c2.x, c2.y));
+                        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
+                        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
                     }
-                    const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
-                    oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
-                    oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
                 }
             }
         }
