@@ -110,8 +110,8 @@ def cpu_baseline(w, x, budget_s: float):
     n = int(max(4 * cores, min(all_u.shape[0], n_pilot * budget_s / max(t_pilot, 1e-3))))
     t, n = run(n)
     rows = n * w.bq / w.n_q_heads          # layer-tokens covered by the sample
-    if w.q_len == 1:
-        value, unit = t / (n / (w.batch * w.n_q_heads)) * 1e6, "us/step"
+    if w.q_len < w.kv_len:
+        value, unit = t / (n / (w.batch * w.n_q_heads * w.n_query_blocks)) * 1e6, "us/step"
     else:
         value, unit = rows / t, "tokens/s"
     return {"value": value, "unit": unit, "cores": cores, "kind": "oracle",
@@ -124,7 +124,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "pd", "ps"])
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 disables")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--calib-copy", action="store_true",
@@ -193,7 +193,7 @@ def main():
     if ms_mask >= ms_attn:
         roof = {"kernel": "mask_estimate", "bound": "hbm", "achieved": mask_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{args.workload}")}
-    elif w.q_len == 1:
+    elif w.q_len == 1:  # vector x matrix: bandwidth bound
         roof = {"kernel": "sparse_attn", "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": attn_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"sparse_attn_{args.workload}")}
     else:
@@ -201,7 +201,7 @@ def main():
                 "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": read_traffic(f"sparse_attn_{args.workload}")}
 
-    if w.q_len == 1:
+    if w.q_len < w.kv_len:  # decode: one (or, for speculative decoding, a few) new rows per sequence
         metric, unit, value, hib = f"HiP decode us/step @{w.kv_len // 1024}k ctx", "us/step", ms_step * 1e3, False
     else:
         metric, unit, value, hib = (f"HiP prefill tokens/s @T={w.kv_len // 1024}k", "tokens/s",

@@ -79,7 +79,12 @@ C4 = Workload("c4_prefill_1m_bf16", 1, 32, 8, 128, 1048576, 1048576, 2048, 64, 4
               seed=SEED_BASE + 4)
 C5 = Workload("c5_ragged_paged_decode_bf16", 256, 32, 8, 128, 1, 65536, 512, 1, 2, "bf16", rho=0.9,
               ragged=(8192, 65536), page_size=64, seed=SEED_BASE + 5)
-WORKLOADS = {w.name.split("_")[0]: w for w in (C1, C2, C3, C4, C5)}
+# The two latency workloads of the paper's block-size ablation (LLaMA-2-7B-32k-shaped layer: 32 MHA heads,
+# d=128, T=12k, batch 96, k=512, mask re-estimated every step): single-query decode and decode with 32
+# query rows per sequence (speculative decoding).
+PD = Workload("pd_paper_decode_12k_bf16", 96, 32, 32, 128, 1, 12288, 512, 1, 2, "bf16", rho=0.9, seed=SEED_BASE + 6)
+PS = Workload("ps_paper_specdec_12k_bf16", 96, 32, 32, 128, 32, 12288, 512, 32, 2, "bf16", rho=0.9, seed=SEED_BASE + 7)
+WORKLOADS = {w.name.split("_")[0]: w for w in (C1, C2, C3, C4, C5, PD, PS)}
 
 
 def scaled(w: Workload, **kw) -> Workload:

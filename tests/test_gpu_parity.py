@@ -70,6 +70,17 @@ def test_prefill_paged(flags, integer):
     U.run_case(w, flags, units=units)
 
 
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("q_len,bq", [(32, 32), (100, 32), (64, 64), (7, 4)])
+def test_chunk_of_queries_over_long_context(flags, q_len, bq):
+    # q_len < kv_len: the last q_len positions of each sequence are queried (chunked prefill, or decode
+    # with several query rows per sequence as in speculative decoding); ragged lengths
+    for integer in (True, False):
+        w = synth.Workload("chunk", 3, 8, 2, 128, q_len, 5000, 256, bq, 2, "bf16", rho=0.9, ragged=(600, 5000),
+                           integer=integer, seed=55)
+        U.run_case(w, flags)
+
+
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_decode_large_batch(integer):
     # >= 4096 (sequence, head) problems selects the shallow-stage decode variant
