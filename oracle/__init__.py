@@ -39,7 +39,7 @@ class _Problem(ctypes.Structure):
         ("k", ctypes.c_int32), ("bq", ctypes.c_int32), ("bk", ctypes.c_int32),
         ("kv_lens", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
         ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
-        ("n_threads", ctypes.c_int32),
+        ("n_threads", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
     ]
 
 
@@ -82,6 +82,8 @@ class Problem:
     page_table: Optional[np.ndarray] = None   # int32 [batch, max_pages]
     page_size: int = 0
     n_threads: int = 1
+    n_sink: int = 0      # sparse attention: the first n_sink keys are always attended
+    n_window: int = 0    # sparse attention: the n_window most recent keys are always attended
 
     @property
     def kb(self) -> int:
@@ -94,7 +96,8 @@ class Problem:
     def _c(self):
         keep = []
         p = _Problem(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.q_len,
-                     self.max_kv_len, self.k, self.bq, self.bk, None, None, 0, 0, self.n_threads)
+                     self.max_kv_len, self.k, self.bq, self.bk, None, None, 0, 0, self.n_threads,
+                     self.n_sink, self.n_window)
         if self.kv_lens is not None:
             a = np.ascontiguousarray(self.kv_lens, dtype=np.int32)
             assert a.shape == (self.batch,)

@@ -44,6 +44,7 @@ typedef struct {
     const int32_t *page_table; /* [batch, max_pages] or NULL => contiguous K/V      */
     int32_t page_size, max_pages;
     int32_t n_threads;         /* OpenMP threads for the batched calls (<=0: default) */
+    int32_t n_sink, n_window;  /* sparse attention only: always-attended first keys / most recent keys */
 } oracle_problem;
 
 /* Statistics of one mask-estimation unit, used by the structural pins. */
@@ -172,42 +173,67 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
 /* top-k masked attention for one (sequence, query head, query block) Eq. 2-3 */
 /* ------------------------------------------------------------------------ */
 
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Key set of a row at position pos (Eq. 2-3 with the mask given by the selected blocks), optionally
+ * united with the first n_sink keys ("global sink") and the n_window most recent keys ("local
+ * sliding window"), which the paper adds in its block-sparse attention kernel (appendix, "Block
+ * Sparse Flash Attention").  Every key counts once.
+ */
 static void attn_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K, const kv_view *V,
-                      int64_t kv_len, const int32_t *idx, int kb, int bk, double sm_scale, double *o)
+                      int64_t kv_len, const int32_t *idx, int kb, int bk, double sm_scale,
+                      int64_t n_sink, int64_t n_window, double *o)
 {
     const int d = K->d;
-    double *s = malloc(sizeof(double) * (size_t)kb * (size_t)bk);
-    int64_t *ts = malloc(sizeof(int64_t) * (size_t)kb * (size_t)bk);
     for (int m = 0; m < n_rows; ++m) {
         const float *qrow = q + (int64_t)m * d;
         double *orow = o + (int64_t)m * d;
+        const int64_t pos = pos0 + m;
         for (int c = 0; c < d; ++c) orow[c] = 0.0;
-        /* admissible keys of this row: selected blocks, within the length, not in the future */
-        int nk = 0;
-        double mx = -INFINITY;
+        if (pos < 0) continue;
+        const int64_t vis = pos + 1 < kv_len ? pos + 1 : kv_len; /* keys [0, vis) are admissible */
+        const int64_t ns = n_sink < vis ? n_sink : vis;
+        const int64_t w0 = vis - n_window > 0 ? vis - n_window : 0;
+        size_t cap = (size_t)kb * (size_t)bk + (size_t)(ns > 0 ? ns : 0) + (size_t)(vis - w0) + 1;
+        int64_t *ts = malloc(sizeof(int64_t) * cap);
+        double *s = malloc(sizeof(double) * cap);
+        size_t nk = 0;
         for (int j = 0; j < kb; ++j) {
             if (idx[j] < 0 || (int64_t)idx[j] >= kv_len) continue; /* sentinel / no block */
             for (int kk = 0; kk < bk; ++kk) {
                 int64_t t = (int64_t)idx[j] + kk;
-                if (t >= kv_len || t > pos0 + m) continue;
-                const float *krow = kv_row(K, t);
-                double dot = 0.0;
-                for (int c = 0; c < d; ++c) dot += (double)qrow[c] * (double)krow[c];
-                s[nk] = sm_scale * dot; ts[nk] = t;
-                if (s[nk] > mx) mx = s[nk];
-                ++nk;
+                if (t < vis) ts[nk++] = t;
             }
         }
-        if (nk == 0) continue; /* no admissible key: the row's output is zero */
-        double den = 0.0;
-        for (int i = 0; i < nk; ++i) { s[i] = exp(s[i] - mx); den += s[i]; }
-        for (int i = 0; i < nk; ++i) {
-            const float *vrow = kv_row(V, ts[i]);
-            double p = s[i] / den;
-            for (int c = 0; c < d; ++c) orow[c] += p * (double)vrow[c];
+        for (int64_t t = 0; t < ns; ++t) ts[nk++] = t;
+        if (n_window > 0) for (int64_t t = w0; t < vis; ++t) ts[nk++] = t;
+        qsort(ts, nk, sizeof(int64_t), cmp_i64);
+        size_t nu = 0;
+        for (size_t i = 0; i < nk; ++i)
+            if (nu == 0 || ts[i] != ts[nu - 1]) ts[nu++] = ts[i];
+        if (nu == 0) { free(ts); free(s); continue; } /* no admissible key: the row's output is zero */
+        double mx = -INFINITY;
+        for (size_t i = 0; i < nu; ++i) {
+            const float *krow = kv_row(K, ts[i]);
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += (double)qrow[c] * (double)krow[c];
+            s[i] = sm_scale * dot;
+            if (s[i] > mx) mx = s[i];
         }
+        double den = 0.0;
+        for (size_t i = 0; i < nu; ++i) { s[i] = exp(s[i] - mx); den += s[i]; }
+        for (size_t i = 0; i < nu; ++i) {
+            const float *vrow = kv_row(V, ts[i]);
+            double pr = s[i] / den;
+            for (int c = 0; c < d; ++c) orow[c] += pr * (double)vrow[c];
+        }
+        free(ts); free(s);
     }
-    free(s); free(ts);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -296,6 +322,7 @@ int oracle_hip_sparse_attn_units(const oracle_problem *p, const float *Q, const 
         kv_view kk = make_view(p, K, b, h / g), vv = make_view(p, V, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
         attn_unit(q, n_rows, pos0, &kk, &vv, kv_len, idx + u * kb, kb, p->bk, sm_scale,
+                  p->n_sink > 0 ? p->n_sink : 0, p->n_window > 0 ? p->n_window : 0,
                   O + u * (int64_t)p->bq * d);
     }
     return 0;

@@ -11,6 +11,8 @@ Each test names the passage of the paper, or the mathematical fact, it checks:
   P6  invariants; a bq=1 prefill row equals a decode call at the same position (Alg. 2)
   P7  sparse attention with an arbitrary index set == dense attention with an additive -inf mask
   P8  on AR(1) keys HiP recalls more of the exact top-k than uniformly random blocks (Sec. 4)
+  P9  sink + sliding window (appendix "Block Sparse Flash Attention"): a window covering everything is dense
+      causal attention; selected blocks + sink + window == dense attention with the union as additive mask
 """
 import math
 import os
@@ -327,6 +329,56 @@ def test_p7_sparse_attention_equals_masked_dense(bq, bk):
     pr = torch.where(empty, torch.zeros_like(pr), pr)
     ref = torch.einsum("bhij,bhjd->bhid", pr, tv.repeat_interleave(g, 1))
     assert bool(empty.any())                       # rows without any admissible key give zeros
+    np.testing.assert_allclose(O, ref.numpy(), rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- P9
+def test_p9_window_covering_everything_is_dense():
+    rng = np.random.default_rng(13)
+    B, hq, hkv, d, T, bq, bk, kb = 1, 2, 1, 16, 45, 4, 2, 3
+    p = Problem(B, hq, hkv, d, T, T, kb * bk, bq, bk, n_window=T)
+    Q, K, V = (_rand((B, h, T, d), rng) for h in (hq, hkv, hkv))
+    idx = np.full((B, hq, p.n_query_blocks, kb), SENTINEL, dtype=np.int32)
+    O = oracle.sparse_attn(p, Q, K, V, idx)
+    tq, tk, tv = (torch.from_numpy(x).double() for x in (Q, K, V))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk.repeat_interleave(2, 1), tv.repeat_interleave(2, 1),
+                                                           is_causal=True)
+    np.testing.assert_allclose(O, ref.numpy(), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("n_sink,n_window,q_len", [(4, 8, 70), (0, 5, 70), (3, 0, 70), (7, 16, 9), (100, 3, 70)])
+def test_p9_sink_window_union_equals_masked_dense(n_sink, n_window, q_len):
+    rng = np.random.default_rng(14)
+    B, hq, hkv, d, T, bq, bk, kb = 2, 2, 2, 8, 70, 4, 2, 4
+    lens = np.array([70, 41 if q_len <= 41 else 70], dtype=np.int32)
+    p = Problem(B, hq, hkv, d, q_len, T, kb * bk, bq, bk, kv_lens=lens, n_sink=n_sink, n_window=n_window)
+    Q = _rand((B, hq, q_len, d), rng)
+    K, V = _rand((B, hkv, T, d), rng), _rand((B, hkv, T, d), rng)
+    nqb = p.n_query_blocks
+    idx = np.full((B, hq, nqb, kb), SENTINEL, dtype=np.int32)
+    mask = np.full((B, hq, q_len, T), -np.inf)
+    for b in range(B):
+        L = int(lens[b])
+        for h in range(hq):
+            for qb in range(nqb):
+                n = int(rng.integers(0, kb + 1))
+                sel = np.sort(rng.choice(-(-L // bk), size=n, replace=False)) * bk
+                idx[b, h, qb, :n] = sel
+                for i in range(qb * bq, min((qb + 1) * bq, q_len)):
+                    pos = L - q_len + i
+                    keys = {t for s0 in sel for t in range(s0, min(s0 + bk, L))}
+                    keys |= set(range(min(n_sink, L)))
+                    keys |= set(range(max(0, pos - n_window + 1), pos + 1))
+                    for t in keys:
+                        if t <= pos and t < L:
+                            mask[b, h, i, t] = 0.0
+    O = oracle.sparse_attn(p, Q, K, V, idx, sm_scale=0.5)
+    tq, tk, tv = (torch.from_numpy(x).double() for x in (Q, K, V))
+    s = torch.einsum("bhid,bhjd->bhij", tq, tk) * 0.5 + torch.from_numpy(mask)
+    empty = torch.isinf(s).all(-1, keepdim=True)
+    pr = torch.softmax(torch.where(empty, torch.zeros_like(s), s), -1)
+    pr = torch.where(empty, torch.zeros_like(pr), pr)
+    ref = torch.einsum("bhij,bhjd->bhid", pr, tv)
     np.testing.assert_allclose(O, ref.numpy(), rtol=0, atol=1e-12)
 
 
