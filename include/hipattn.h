@@ -46,7 +46,8 @@ extern "C" {
 enum {
     HIP_ATTN_OK = 0,
     HIP_ATTN_ENULL = -1,       /* a required pointer is NULL                                  */
-    HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len   */
+    HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len,  */
+                               /* negative n_sink / n_window                                  */
     HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1    */
     HIP_ATTN_EHEADDIM = -4,    /* head_dim not in {64, 128}                                   */
     HIP_ATTN_EDTYPE = -5,      /* dtype not HIP_ATTN_F32 / HIP_ATTN_BF16                      */
@@ -84,6 +85,12 @@ typedef struct hip_problem {
      * head_dim] where kv_strides[0] is the page stride.  Row strides must keep rows 16-byte
      * aligned. */
     int64_t q_strides[3], kv_strides[3], o_strides[3];
+    /* hip_sparse_attn only (paper appendix "Block Sparse Flash Attention": a global sink and a small
+     * sliding window are attended in addition to the selected blocks): every row also attends to the
+     * first n_sink keys and to the n_window most recent keys up to its own position; each key counts
+     * once.  0 = off.  With a window that covers the steps since the last hip_mask_estimate call, an
+     * index array from an earlier (shorter) kv_len may be reused as is (Alg. 2, mask refresh period). */
+    int32_t n_sink, n_window;
 } hip_problem;
 
 /*
@@ -107,8 +114,9 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
  *   indices  as written by hip_mask_estimate; any entry < 0 or >= kv_len means "no block";
  *            valid entries of a row must be distinct.
  *   O        device, layout per o_strides, same dtype as Q.  Row i attends to the keys t of
- *            its query block's selected blocks with t < kv_len and t <= pos(i); a row with no
- *            such key is written as zeros.  Softmax statistics and accumulation are fp32.
+ *            its query block's selected blocks (plus sink and window keys, see hip_problem) with
+ *            t < kv_len and t <= pos(i); a row with no such key is written as zeros.  Softmax
+ *            statistics and accumulation are fp32.
  */
 int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const void *V,
                     const int32_t *indices, void *O, void *stream);

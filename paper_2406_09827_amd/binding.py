@@ -31,6 +31,7 @@ class HipProblem(ctypes.Structure):
         ("kv_lens", ctypes.c_void_p), ("page_table", ctypes.c_void_p),
         ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
         ("q_strides", ctypes.c_int64 * 3), ("kv_strides", ctypes.c_int64 * 3), ("o_strides", ctypes.c_int64 * 3),
+        ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
     ]
 
 
@@ -135,8 +136,9 @@ def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=N
 
 def hip_sparse_attn(Q, K, V, indices, k: int, bq: int, bk: int, kv_lens=None, page_table=None,
                     max_kv_len=None, sm_scale: float = 0.0, flags: int = 0,
-                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """O [B, Hq, Tq, d]: attention of every query row over its block's selected keys."""
+                    out: Optional[torch.Tensor] = None, n_sink: int = 0, n_window: int = 0) -> torch.Tensor:
+    """O [B, Hq, Tq, d]: attention of every query row over its block's selected keys (plus the first
+    n_sink and the n_window most recent keys)."""
     _need_gpu(Q, K, V, indices, kv_lens, page_table, out)
     lib = load()
     assert V.shape == K.shape and V.stride() == K.stride() and V.dtype == K.dtype == Q.dtype
@@ -145,6 +147,7 @@ def hip_sparse_attn(Q, K, V, indices, k: int, bq: int, bk: int, kv_lens=None, pa
     assert out.shape == Q.shape and out.dtype == Q.dtype and out.stride(3) == 1
     assert indices.dtype == torch.int32 and indices.is_contiguous()
     p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, sm_scale, flags, O=out)
+    p.n_sink, p.n_window = n_sink, n_window
     rc = lib.hip_sparse_attn(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), indices.data_ptr(),
                              out.data_ptr(), _stream(Q))
     if rc != 0:

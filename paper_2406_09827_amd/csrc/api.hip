@@ -17,6 +17,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     if (p.batch < 0 || p.n_q_heads <= 0 || p.n_kv_heads <= 0 || p.q_len < 0 || p.max_kv_len < 0) return HIP_ATTN_ESHAPE;
     if (p.n_q_heads % p.n_kv_heads) return HIP_ATTN_ESHAPE;
     if (p.q_len > p.max_kv_len) return HIP_ATTN_ESHAPE;
+    if (p.n_sink < 0 || p.n_window < 0) return HIP_ATTN_ESHAPE;
     if (p.head_dim != 64 && p.head_dim != 128) return HIP_ATTN_EHEADDIM;
     if (p.dtype != HIP_ATTN_F32 && p.dtype != HIP_ATTN_BF16) return HIP_ATTN_EDTYPE;
     if (p.k <= 0 || p.bk <= 0 || p.bq <= 0 || p.k % p.bk) return HIP_ATTN_EBLOCK;
@@ -35,6 +36,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.kb = p.k / p.bk; kp.bq = p.bq; kp.bk = p.bk; kp.nqb = nqb;
     kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
+    kp.n_sink = p.n_sink; kp.n_window = p.n_window;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
         for (kp.page_shift = 0; (1 << kp.page_shift) < p.page_size;) ++kp.page_shift;

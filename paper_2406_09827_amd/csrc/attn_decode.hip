@@ -37,15 +37,41 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 
     // one stage = U blocks per lane group: BK key rows and BK value rows each, loaded
     // unconditionally (a block that does not count re-reads row 0 and gets probability 0).
-    auto fetch = [&](int base, stage_t &kr, stage_t &vr, int (&first)[U]) __attribute__((always_inline)) {
-        int pg[U];
+    // Block list: the kb selected blocks, then the sink range, then the window range cut into
+    // BK-aligned blocks.  Rows of a block count iff lo <= position < hi:
+    //   selected [n_sink, w0), sink [0, ns), window [w0, kv_len), with w0 = kv_len - n_window.
+    const int w0 = max(kv_len - p.n_window, 0);
+    const int ns = min(p.n_sink, w0);
+    const int nb_sink = (ns + BK - 1) / BK;
+    const int win_first = (w0 / BK) * BK;
+    const int nb_win = p.n_window > 0 ? (kv_len - win_first + BK - 1) / BK : 0;
+    const int n_blocks = kb + nb_sink + nb_win;
+
+    // one stage = U blocks per lane group: BK key rows and BK value rows each, loaded
+    // unconditionally (a block that does not count re-reads row 0 and gets probability 0).
+    // okm[u]: bit n set iff row n of block u counts
+    auto fetch = [&](int base, stage_t &kr, stage_t &vr, int (&okm)[U]) __attribute__((always_inline)) {
+        int pg[U], first[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = base + u * RPW + grp;
-            int f = -1;
-            if (j < kb) f = idx[j];
-            if (f >= kv_len) f = -1;
+            int f = -1, lo = 0, hi = 0;
+            if (j < kb) {
+                f = idx[j];
+                if (f >= kv_len) f = -1;
+                lo = p.n_sink; hi = w0;
+            } else if (j < kb + nb_sink) {
+                f = (j - kb) * BK;
+                hi = ns;
+            } else if (j < n_blocks) {
+                f = win_first + (j - kb - nb_sink) * BK;
+                lo = w0; hi = kv_len;
+            }
             first[u] = f;
+            int m = 0;
+#pragma unroll
+            for (int n = 0; n < BK; ++n) m |= (f >= 0 && f + n >= lo && f + n < hi) ? (1 << n) : 0;
+            okm[u] = m;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) pg[u] = page_of_row<PAGED>(p, b, first[u] >= 0 ? first[u] : 0);
@@ -64,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
             }
         }
     };
-    auto consume = [&](const stage_t &kr, const stage_t &vr, const int (&first)[U]) __attribute__((always_inline)) {
+    auto consume = [&](const stage_t &kr, const stage_t &vr, const int (&okm)[U]) __attribute__((always_inline)) {
         float s[U][BK], mx = -INFINITY;
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -73,8 +99,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
                 const int q4 = 4 * (u * BK + n);
                 const float d = row_group_sum<LPR>(dot8_bf16(qv, make_uint4(kr[q4], kr[q4 + 1], kr[q4 + 2], kr[q4 + 3]))) * c;
                 // the query is the last position of its sequence: no key is in its future
-                const bool ok = first[u] >= 0 && first[u] + n < kv_len;
-                s[u][n] = ok ? d : -INFINITY;
+                s[u][n] = ((okm[u] >> n) & 1) ? d : -INFINITY;
                 mx = fmaxf(mx, s[u][n]);
             }
         const float m_new = fmaxf(m_run, mx);
@@ -103,12 +128,12 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
     stage_t ka, va, kb2, vb2;
     int fa[U], fb[U];
     fetch(0, ka, va, fa);
-    for (int base = 0; base < kb; base += 2 * STEP) {
-        const bool has_b = base + STEP < kb;
+    for (int base = 0; base < n_blocks; base += 2 * STEP) {
+        const bool has_b = base + STEP < n_blocks;
         if (has_b) fetch(base + STEP, kb2, vb2, fb);
         consume(ka, va, fa);
         if (has_b) {
-            if (base + 2 * STEP < kb) fetch(base + 2 * STEP, ka, va, fa);
+            if (base + 2 * STEP < n_blocks) fetch(base + 2 * STEP, ka, va, fa);
             consume(kb2, vb2, fb);
         }
     }

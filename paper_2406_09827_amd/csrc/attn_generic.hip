@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(KParams p)
 
     const T *Kbase = (const T *)p.K, *Vbase = (const T *)p.V;
     T *Ob = (T *)p.O + (int64_t)b * p.os_b + (int64_t)h * p.os_h + (int64_t)row0 * p.os_r;
-    const int n_keys = kb * bk;
+    const int n_sel = kb * bk;
 
     for (int m = wave; m < n_rows; m += kThreads / 64) {
         const float *qrow = q_s + m * D;
@@ -55,16 +55,29 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(KParams p)
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
 
+        // keys of this row: [0, vis) are admissible; the window takes [w0, vis), the sink takes
+        // [0, ns) below the window, the selected blocks contribute what lies in [ns, w0)
+        const int vis = min(pos0 + m + 1, kv_len);
+        const int w0 = max(vis - p.n_window, 0);
+        const int ns = min(p.n_sink, w0);
+        const int n_keys = vis > 0 ? n_sel + ns + (vis - w0) : 0;
+
         for (int base = 0; base < n_keys; base += 64) {
             const int ki = base + lane;
             bool valid = ki < n_keys;
             int t = 0;
             if (valid) {
-                const int j = ki / bk, n = ki - j * bk;
-                const int first = idx[j];
-                valid = first >= 0 && first < kv_len;
-                t = valid ? first + n : 0;
-                valid = valid && t < kv_len && t <= pos0 + m;
+                if (ki < n_sel) {
+                    const int j = ki / bk, n = ki - j * bk;
+                    const int first = idx[j];
+                    valid = first >= 0 && first < kv_len;
+                    t = valid ? first + n : 0;
+                    valid = valid && t >= ns && t < w0;
+                } else if (ki < n_sel + ns) {
+                    t = ki - n_sel;
+                } else {
+                    t = w0 + (ki - n_sel - ns);
+                }
             }
             int64_t off = 0;
             float s = -INFINITY;

@@ -81,7 +81,19 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int pos0 = kv_len - p.q_len + row0;  // position of this tile's first query row
     const int32_t *idx = p.idx_in + (((int64_t)b * p.hq + h) * p.nqb + qb) * p.kb;
     const int bk = 1 << log_bk;
-    const int n_keys = p.kb << log_bk, n_tiles = (n_keys + 31) >> 5;
+    // Key tiles: first the selected blocks, then the sink keys [0, ns), then the window keys
+    // [wlo, vis_last).  For a row at position q with vis = min(q+1, kv_len) and
+    // w0 = max(vis - n_window, 0): a selected or sink key t counts iff t < w0 (selected also
+    // t >= n_sink), a window key iff w0 <= t < vis - so every key counts once.
+    const int n_keys = p.kb << log_bk;
+    const int vis_last = min(pos0 + n_rows, kv_len);                     // keys any row of the tile may see
+    const int wlo = max(min(pos0 + 1, kv_len) - p.n_window, 0);          // window start of the first row
+    const int ns = min(p.n_sink, max(vis_last - p.n_window, 0));         // sink keys some row takes as sink
+    const int nw = p.n_window > 0 ? max(vis_last - wlo, 0) : 0;
+    const int tiles_sel = (n_keys + 31) >> 5, tiles_sink = (ns + 31) >> 5, tiles_win = (nw + 31) >> 5;
+    const int n_tiles = tiles_sel + tiles_sink + tiles_win;
+    const int w0_first = wlo;                                             // smallest w0 over the rows
+    const int w0_last = max(vis_last - p.n_window, 0);                    // largest w0 over the rows
 
     // ---- query tile as B operand (lane: query col, channels kk*16 + hh*8 ..)
     bf16x8 qf[KS];
@@ -111,15 +123,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     // One tile of 32 gathered keys: lane `col` works out key row col (position or -1, row
     // offset in 16-byte units), publishes both, then every lane loads its share of the key and
     // value rows coalesced.  Rows that do not count load row 0 of the sequence (always mapped,
-    // finite) and get probability 0.  Returns flags: bit 0 = some key is visible to some row,
-    // bit 1 = some (key, row) pair needs masking.
+    // finite) and get probability 0.  Returns flags: bit 0 = some key may count for some row,
+    // bit 1 = some (key, row) pair needs masking, bit 2 = window tile.
     auto fetch = [&](int tile, stage_t &RK, stage_t &RV, int *tk) __attribute__((always_inline)) {
-        const int ki = tile * 32 + col;
         int t_c = -1;
-        if (ki < n_keys) {
-            const int first = idx[ki >> log_bk];
-            const int t = first + (ki & (bk - 1));
-            if (first >= 0 && first < kv_len && t < kv_len) t_c = t;
+        int flags;
+        if (tile < tiles_sel) {
+            const int ki = tile * 32 + col;
+            if (ki < n_keys) {
+                const int first = idx[ki >> log_bk];
+                const int t = first + (ki & (bk - 1));
+                if (first >= 0 && first < kv_len && t < kv_len && t >= p.n_sink) t_c = t;
+            }
+            flags = (__ballot(t_c >= 0 && t_c < w0_last) != 0 ? 1 : 0) | (__ballot(t_c < 0 || t_c >= w0_first) != 0 ? 2 : 0);
+        } else if (tile < tiles_sel + tiles_sink) {
+            const int t = (tile - tiles_sel) * 32 + col;
+            if (t < ns) t_c = t;
+            flags = 1 | 2;
+        } else {
+            const int t = wlo + (tile - tiles_sel - tiles_sink) * 32 + col;
+            if (t < vis_last) t_c = t;
+            flags = 1 | 2 | 4;  // bit 2: window tile (keys count for the rows whose window holds them)
         }
         {
             const int tr = t_c >= 0 ? t_c : 0;
@@ -129,8 +153,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 mo[col] = (uint32_t)(eo >> 3);
             }
         }
-        const int flags = (__ballot(t_c >= 0 && t_c <= pos0 + n_rows - 1) != 0 ? 1 : 0) |
-                          (__ballot(t_c < 0 || t_c > pos0) != 0 ? 2 : 0);
         wave_lds_sync();
         uint32_t off[NLD];
 #pragma unroll
@@ -179,15 +201,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             // ---- online softmax for query `col` (both half-waves hold the same query)
             float s[16], mx = -INFINITY;
             if (flags & 2) {
-                // positions of the 16 keys this lane holds scores for: rows 8g + 4hh + {0..3}
-                const int qpos = pos0 + col;
+                // positions of the 16 keys this lane holds scores for: rows 8g + 4hh + {0..3};
+                // admissible range [lo, hi) of key positions for this lane's query
+                const int visq = min(pos0 + col + 1, kv_len);
+                const int w0q = max(visq - p.n_window, 0);
+                const int lo = (flags & 4) ? w0q : 0, hi = (flags & 4) ? visq : w0q;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int4 tq = *(const int4 *)(tk + 8 * g + 4 * hh);
                     const int tkey[4] = {tq.x, tq.y, tq.z, tq.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const bool ok = tkey[e] >= 0 && tkey[e] <= qpos;
+                        const bool ok = tkey[e] >= lo && tkey[e] < hi;
                         s[4 * g + e] = ok ? sacc[4 * g + e] * c : -INFINITY;
                     }
                 }

@@ -21,6 +21,7 @@ struct KParams {
     int64_t os_b, os_h, os_r;
     int32_t batch, hq, hkv, g, d, q_len, max_kv_len, kb, bq, bk, nqb, page_size, max_pages;
     int32_t page_shift;        // log2(page_size) when it is a power of two, else -1
+    int32_t n_sink, n_window;  // sparse attention: always-attended first / most recent keys
     float sm_scale;
 };
 

@@ -11,11 +11,12 @@ import paper_2406_09827_amd as hipattn
 from paper_2406_09827_amd import synth
 
 
-def oracle_problem(w, x, n_threads=8):
+def oracle_problem(w, x, n_threads=8, n_sink=0, n_window=0):
     lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
     table = x["page_table"].cpu().numpy() if x["page_table"] is not None else None
     return oracle.Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
-                          kv_lens=lens, page_table=table, page_size=w.page_size, n_threads=n_threads)
+                          kv_lens=lens, page_table=table, page_size=w.page_size, n_threads=n_threads,
+                          n_sink=n_sink, n_window=n_window)
 
 
 def host(x):
@@ -32,9 +33,10 @@ def gpu_mask(w, x, flags=0):
                                      page_table=x["page_table"], max_kv_len=_max_len(w, x), flags=flags)
 
 
-def gpu_attn(w, x, idx, flags=0, sm_scale=0.0):
+def gpu_attn(w, x, idx, flags=0, sm_scale=0.0, n_sink=0, n_window=0):
     return hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
-                                   page_table=x["page_table"], max_kv_len=_max_len(w, x), sm_scale=sm_scale, flags=flags)
+                                   page_table=x["page_table"], max_kv_len=_max_len(w, x), sm_scale=sm_scale, flags=flags,
+                                   n_sink=n_sink, n_window=n_window)
 
 
 def check_output(got, ref, dtype):
@@ -54,14 +56,14 @@ def agreement(a, b):
     return float((a == b).mean())
 
 
-def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0):
+def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_window=0):
     """Full comparison of one workload; returns (agreement, max output error)."""
     exact = w.integer if exact is None else exact
     x = synth.make_inputs(w, device="cuda", threads=4)
     idx_gpu = gpu_mask(w, x, flags)
-    out_gpu = gpu_attn(w, x, idx_gpu, flags, sm_scale)
+    out_gpu = gpu_attn(w, x, idx_gpu, flags, sm_scale, n_sink, n_window)
     torch.cuda.synchronize()
-    p = oracle_problem(w, x)
+    p = oracle_problem(w, x, n_sink=n_sink, n_window=n_window)
     hx = host(x)
     all_u = oracle.all_units(p)
     if units is None:

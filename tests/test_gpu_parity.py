@@ -139,3 +139,53 @@ def test_empty_batch_and_strided_views():
     oa = hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], a, w.k, w.bq, w.bk)
     ob = hipattn.hip_sparse_attn(Qt, Kt, Vt, a, w.k, w.bq, w.bk, out=torch.empty_like(Qt))
     assert torch.equal(oa, ob)
+
+
+# ---- sink + sliding window in the sparse attention, mask reuse across decode steps -------------
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("n_sink,n_window", [(4, 64), (128, 16), (0, 100), (33, 0), (5000, 7)])
+def test_prefill_sink_window(flags, n_sink, n_window):
+    w = synth.scaled(synth.C2, q_len=3000 + 17, kv_len=3000 + 17, n_q_heads=4, n_kv_heads=2, k=256, spike_every=1024)
+    nqb = w.n_query_blocks
+    units = [(0, h, qb) for h in range(4) for qb in (0, 1, 2, 3, 4, 5, 9, 40, nqb - 2, nqb - 1)]
+    U.run_case(w, flags, units=units, n_sink=n_sink, n_window=n_window)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+def test_prefill_sink_window_fp32_and_big_blocks(flags):
+    U.run_case(synth.C1, flags, n_sink=8, n_window=48)
+    w = synth.scaled(synth.C4, q_len=4096 + 70, kv_len=4096 + 70, n_q_heads=2, n_kv_heads=1, k=512)
+    nqb = w.n_query_blocks
+    U.run_case(w, flags, units=[(0, h, qb) for h in range(2) for qb in (0, 1, 2, 7, 30, nqb - 1)], n_sink=16, n_window=200)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("n_sink,n_window", [(4, 64), (300, 5), (0, 1), (9, 0)])
+def test_decode_sink_window(flags, n_sink, n_window):
+    w = synth.scaled(synth.C5, batch=5, kv_len=7000, ragged=(100, 7000))
+    U.run_case(w, flags, n_sink=n_sink, n_window=n_window)
+    w = synth.scaled(synth.C3, batch=2, kv_len=9000)
+    U.run_case(w, flags, n_sink=n_sink, n_window=n_window)
+
+
+def test_mask_reuse_across_decode_steps():
+    """Alg. 2 with a refresh period: the mask of step 0 serves the next steps; the sliding window
+    covers the tokens appended since.  Each step is checked against the oracle on the same indices."""
+    import oracle
+    import paper_2406_09827_amd as hipattn
+    r_m, n_window, n_sink = 8, 16, 4
+    w = synth.scaled(synth.C3, batch=3, kv_len=6000 + r_m)
+    x = synth.make_inputs(w, device="cuda", threads=2)
+    lens0 = torch.tensor([6000, 3500, 811], dtype=torch.int32, device="cuda")
+    hx = U.host(x)
+    idx = None
+    for step in range(r_m):
+        lens = (lens0 + step).contiguous()
+        if step == 0:
+            idx = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, 1, w.bk, kv_lens=lens)
+        out = hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, 1, w.bk, kv_lens=lens, n_sink=n_sink, n_window=n_window)
+        p = oracle.Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, 1, w.kv_len, w.k, 1, w.bk,
+                           kv_lens=lens.cpu().numpy(), n_sink=n_sink, n_window=n_window, n_threads=8)
+        ref = oracle.sparse_attn(p, hx["Q"], hx["K"], hx["V"], idx.cpu().numpy())
+        U.check_output(out.float().cpu().numpy(), ref, "bf16")
