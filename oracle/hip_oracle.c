@@ -45,6 +45,10 @@ typedef struct {
     int32_t page_size, max_pages;
     int32_t n_threads;         /* OpenMP threads for the batched calls (<=0: default) */
     int32_t n_sink, n_window;  /* sparse attention only: always-attended first keys / most recent keys */
+    /* mask estimation only: sampling strides inside the block score (Sec. 3.2, last paragraph) and the
+     * position of a branch's representative block (Sec. 3.1 uses the centre; the appendix ablates others) */
+    int32_t b_sq, b_sk;        /* <= 1: every query row / every key of the block */
+    int32_t rep_pos;           /* 0 centre, 1 first block, 2 last block of the branch */
 } oracle_problem;
 
 /* Statistics of one mask-estimation unit, used by the structural pins. */
@@ -86,8 +90,10 @@ static int64_t rnd_div(int64_t a, int64_t b) { return (2 * a + b) / (2 * b); }
  *          then ORACLE_SENTINEL padding
  */
 static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K, int64_t kv_len,
-                      int kb, int bk, int32_t *out, oracle_mask_stats *st)
+                      int kb, int bk, int b_sq, int b_sk, int rep_pos, int32_t *out, oracle_mask_stats *st)
 {
+    if (b_sq < 1) b_sq = 1;
+    if (b_sk < 1) b_sk = 1;
     const int d = K->d;
     for (int j = 0; j < kb; ++j) out[j] = ORACLE_SENTINEL;
     if (st) { st->rounds = 0; st->first_chunk_max = 0; st->reps_scored = 0; }
@@ -131,13 +137,13 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
         /* Score each branch by its centre key block: max over the block's query rows and
          * the block's keys of the causally admissible dot products (Sec. 3.2, Alg. 1). */
         for (int b = 0; b < nb; ++b) {
-            int64_t r = bs[b] + (be[b] - bs[b]) / 2;
+            int64_t r = rep_pos == 1 ? bs[b] : rep_pos == 2 ? be[b] - 1 : bs[b] + (be[b] - bs[b]) / 2;
             double best = -INFINITY;
-            for (int kk = 0; kk < bk; ++kk) {
+            for (int kk = 0; kk < bk; kk += b_sk) {      /* every b_sk-th key of the block */
                 int64_t t = r * bk + kk;
                 if (t >= kv_len) continue;
                 const float *krow = kv_row(K, t);
-                for (int m = 0; m < n_rows; ++m) {
+                for (int m = 0; m < n_rows; m += b_sq) { /* every b_sq-th row of the query block */
                     if (t > pos0 + m) continue;
                     const float *qrow = q + (int64_t)m * d;
                     double dot = 0.0;
@@ -294,7 +300,8 @@ int oracle_hip_mask_estimate_units(const oracle_problem *p, const float *Q, cons
         int64_t pos0 = kv_len - p->q_len + row0;
         kv_view kv = make_view(p, K, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
-        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, out + u * kb, stats ? stats + u : NULL);
+        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, out + u * kb,
+                  stats ? stats + u : NULL);
     }
     return 0;
 }

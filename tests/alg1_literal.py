@@ -15,7 +15,7 @@ def _round_half_up(x: Fraction) -> int:
     return math.floor(x + Fraction(1, 2))
 
 
-def literal_mask_unit(score_fn, Tb: int, kb: int):
+def literal_mask_unit(score_fn, Tb: int, kb: int, rep_pos: int = 0):
     """score_fn(r) -> score of the 1-based key block r (max over the query block's rows and the
     block's keys of the admissible dot products; -inf if none).  Returns the sorted list of
     selected 1-based block numbers."""
@@ -40,9 +40,11 @@ def literal_mask_unit(score_fn, Tb: int, kb: int):
             if f > l:
                 scores.append(-math.inf)
             else:
-                r = _round_half_up(Fraction(f + l, 2))
+                r = f if rep_pos == 1 else l if rep_pos == 2 else _round_half_up(Fraction(f + l, 2))
                 scores.append(score_fn(r))
-        order = sorted(range(len(branches)), key=lambda h: (-scores[h], h))
+        # an empty range (f > l) never displaces a real one, even one whose score is -inf because
+        # stride sampling left it no admissible (row, key) pair
+        order = sorted(range(len(branches)), key=lambda h: (-scores[h], branches[h][0] > branches[h][1], h))
         top = sorted(order[:kb])
         nodes = [branches[h] for h in top]
     out = sorted(f for (f, l) in nodes if f <= l)

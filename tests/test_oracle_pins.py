@@ -63,7 +63,7 @@ def test_p1_dense_equivalence(T, bq, bk, d, hq, hkv):
 
 
 # ----------------------------------------------------------------------------- P2
-def _literal_indices(p, Q, K, b, h, qb, kv_len):
+def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0):
     """Scores for the literal transcription are formed here from exact rationals of the
     (integer-valued) inputs or from float64 dot products."""
     g = p.n_q_heads // p.n_kv_heads
@@ -79,18 +79,18 @@ def _literal_indices(p, Q, K, b, h, qb, kv_len):
 
     def score(r1):
         best = -math.inf
-        for n in range(p.bk):
+        for n in range(0, p.bk, b_sk):
             t = (r1 - 1) * p.bk + n
             if t >= kv_len:
                 continue
-            for m in range(n_rows):
+            for m in range(0, n_rows, b_sq):
                 if t > pos0 + m:
                     continue
                 s = float(np.dot(Qd[row0 + m], Kd[t]))
                 best = max(best, s)
         return best
 
-    blocks = literal_mask_unit(score, Tb, p.kb)
+    blocks = literal_mask_unit(score, Tb, p.kb, rep_pos)
     return [(r1 - 1) * p.bk for r1 in blocks]
 
 
@@ -148,6 +148,44 @@ def test_p2_gqa_head_mapping():
                 assert _valid(idx[b, h, qb]) == _literal_indices(p, Q, K, b, h, qb, T)
         differ |= not np.array_equal(idx[b, 0], idx[b, 2])
     assert differ
+
+
+@pytest.mark.parametrize("integer", [True, False])
+def test_p2_scoring_variants(integer):
+    """Sampling strides inside the block score (Sec. 3.2) and the representative position, against the
+    literal transcription with the same options; and a case built so that each option changes the result."""
+    rng = np.random.default_rng(31 if integer else 32)
+    d = 4 if integer else 8
+    n = 0
+    for (bq, bk, b_sq, b_sk) in [(4, 4, 2, 2), (8, 2, 4, 2), (4, 4, 1, 4), (2, 1, 2, 1), (6, 4, 3, 2)]:
+        for rep_pos in (0, 1, 2):
+            for kb in (1, 3, 8):
+                for T in (5, 16, 37, 64, 130):
+                    p = Problem(1, 1, 1, d, T, T, kb * bk, bq, bk, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
+                    Q, K = _rand((1, 1, T, d), rng, integer), _rand((1, 1, T, d), rng, integer)
+                    idx = oracle.mask_estimate(p, Q, K)
+                    for qb in sorted({0, p.n_query_blocks // 2, p.n_query_blocks - 1}):
+                        want = _literal_indices(p, Q, K, 0, 0, qb, T, b_sq, b_sk, rep_pos)
+                        assert _valid(idx[0, 0, qb]) == want, (bq, bk, b_sq, b_sk, rep_pos, kb, T, qb)
+                        n += 1
+    assert n > 500
+    # 8 keys, one query at the end, kb = 1, blocks of 2: block maxima 3,4,9,6 but FIRST keys 3,4,5,2
+    K = np.array([3, 1, 4, 1, 5, 9, 2, 6], dtype=np.float32).reshape(1, 1, 8, 1)
+    Q = np.ones((1, 1, 1, 1), dtype=np.float32)
+    full = oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2), Q, K)
+    first_key_only = oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, b_sk=2), Q, K)
+    # [0,4): branches [0,2) centre block 1 (keys 4,1) vs [2,4) centre block 3 (keys 2,6): full max 4 < 6 -> right,
+    # then block 2 (5,9) vs block 3 (2,6) -> block 2 = position 4.  First keys only: 4 > 2 -> left, then 3 < 4 -> position 2.
+    assert _valid(full[0, 0, 0]) == [4] and _valid(first_key_only[0, 0, 0]) == [2]
+    # representative = first block of the branch: [0,2) -> block 0 (3,1) vs [2,4) -> block 2 (5,9): right; then 9 vs 6 -> 4
+    # representative = last block: block 1 (4,1) vs block 3 (2,6): right; then block 2 vs block 3 -> 4
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, rep_pos=1), Q, K)[0, 0, 0]) == [4]
+    K2 = np.array([9, 9, 1, 1, 2, 2, 3, 3], dtype=np.float32).reshape(1, 1, 8, 1)
+    # first-block representative sees the 9 in block 0 and goes left (then block 0 wins): position 0;
+    # centre representative compares block 1 (1) with block 3 (3) and goes right: position 6
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, rep_pos=1), Q, K2)[0, 0, 0]) == [0]
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, rep_pos=0), Q, K2)[0, 0, 0]) == [6]
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, rep_pos=2), Q, K2)[0, 0, 0]) == [6]
 
 
 # ----------------------------------------------------------------------------- P3
