@@ -127,6 +127,10 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "pd", "ps"])
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 disables")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
+    ap.add_argument("--b-sq", type=int, default=1, help="query-row sampling stride of the block score (default: all rows)")
+    ap.add_argument("--b-sk", type=int, default=1, help="key sampling stride of the block score (default: all keys)")
+    ap.add_argument("--n-sink", type=int, default=0, help="sink keys added in the sparse attention (default 0)")
+    ap.add_argument("--n-window", type=int, default=0, help="sliding-window keys added in the sparse attention (default 0)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     args = ap.parse_args()
@@ -153,9 +157,10 @@ def main():
 
     def step():
         hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx)
+                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk)
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
-                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out)
+                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
+                                n_sink=args.n_sink, n_window=args.n_window)
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -174,10 +179,11 @@ def main():
     for i in range(args.steps):
         ev[i][0].record()
         hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx)
+                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk)
         ev[i][1].record()
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
-                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out)
+                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
+                                n_sink=args.n_sink, n_window=args.n_window)
         ev[i][2].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -212,7 +218,8 @@ def main():
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
-                   "kernels": "generic" if args.generic else "tuned"},
+                   "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk,
+                   "n_sink": args.n_sink, "n_window": args.n_window},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
         "mask_estimate": {"algorithmic_GB": mask_bytes / 1e9, "GB/s": mask_gbs, "frac_hbm_peak": mask_gbs / HBM_PEAK_GBS},
         "sparse_attn": {"algorithmic_TFLOP": attn_flops / 1e12, "TFLOP/s": attn_tflops,

@@ -48,7 +48,8 @@ enum {
     HIP_ATTN_ENULL = -1,       /* a required pointer is NULL                                  */
     HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len,  */
                                /* negative n_sink / n_window                                  */
-    HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1    */
+    HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1,   */
+                               /* b_sq > bq, bk % b_sk != 0, unknown rep_pos                  */
     HIP_ATTN_EHEADDIM = -4,    /* head_dim not in {64, 128}                                   */
     HIP_ATTN_EDTYPE = -5,      /* dtype not HIP_ATTN_F32 / HIP_ATTN_BF16                      */
     HIP_ATTN_ETOOLARGE = -6,   /* k/bk above HIP_ATTN_MAX_KB, or bq*head_dim above the limit  */
@@ -58,6 +59,7 @@ enum {
 };
 
 enum { HIP_ATTN_F32 = 0, HIP_ATTN_BF16 = 1 };
+enum { HIP_ATTN_REP_CENTER = 0, HIP_ATTN_REP_FIRST = 1, HIP_ATTN_REP_LAST = 2 };
 
 /* flags */
 enum {
@@ -91,6 +93,15 @@ typedef struct hip_problem {
      * once.  0 = off.  With a window that covers the steps since the last hip_mask_estimate call, an
      * index array from an earlier (shorter) kv_len may be reused as is (Alg. 2, mask refresh period). */
     int32_t n_sink, n_window;
+    /* hip_mask_estimate only: the block score may be taken over a sample of the query block's rows
+     * and of the representative block's keys (paper Sec. 3.2, last paragraph): rows 0, b_sq, 2*b_sq, ...
+     * and keys 0, b_sk, 2*b_sk, ... of the block.  0 or 1 = every row / key.  b_sk must divide bk.
+     * A non-empty branch none of whose sampled (row, key) pairs is admissible scores -inf (it still
+     * outranks an empty branch). */
+    int32_t b_sq, b_sk;
+    /* hip_mask_estimate only: which block of a branch represents it: HIP_ATTN_REP_CENTER (default,
+     * paper Sec. 3.1), _FIRST or _LAST (the paper's appendix ablates the position). */
+    int32_t rep_pos;
 } hip_problem;
 
 /*

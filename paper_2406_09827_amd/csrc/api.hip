@@ -23,6 +23,8 @@ int prepare(const hip_problem *hp, KParams &kp)
     if (p.k <= 0 || p.bk <= 0 || p.bq <= 0 || p.k % p.bk) return HIP_ATTN_EBLOCK;
     if (p.bq > HIP_ATTN_MAX_BQ || p.bk > HIP_ATTN_MAX_BK) return HIP_ATTN_EBLOCK;
     if (p.q_len == 1 && p.bq != 1) return HIP_ATTN_EBLOCK;
+    if (p.b_sq < 0 || p.b_sk < 0 || p.b_sq > p.bq || (p.b_sk > 1 && p.bk % p.b_sk)) return HIP_ATTN_EBLOCK;
+    if (p.rep_pos < HIP_ATTN_REP_CENTER || p.rep_pos > HIP_ATTN_REP_LAST) return HIP_ATTN_EBLOCK;
     if (p.k / p.bk > HIP_ATTN_MAX_KB) return HIP_ATTN_ETOOLARGE;
     if (p.page_table && (p.page_size <= 0 || p.page_size % p.bk || p.max_pages <= 0)) return HIP_ATTN_EPAGE;
     if (p.page_table && (int64_t)p.max_pages * p.page_size < p.max_kv_len) return HIP_ATTN_EPAGE;
@@ -37,6 +39,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
+    kp.b_sq = p.b_sq > 1 ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
         for (kp.page_shift = 0; (1 << kp.page_shift) < p.page_size;) ++kp.page_shift;

@@ -22,6 +22,8 @@ struct KParams {
     int32_t batch, hq, hkv, g, d, q_len, max_kv_len, kb, bq, bk, nqb, page_size, max_pages;
     int32_t page_shift;        // log2(page_size) when it is a power of two, else -1
     int32_t n_sink, n_window;  // sparse attention: always-attended first / most recent keys
+    int32_t b_sq, b_sk;        // mask estimation: row / key sampling strides of the block score (>= 1)
+    int32_t rep_pos;           // mask estimation: representative block of a branch: 0 centre, 1 first, 2 last
     float sm_scale;
 };
 
@@ -87,6 +89,14 @@ __device__ __forceinline__ int lane_prefix_count(uint64_t mask)
 {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
+
+// Representative block of the branch [bs, be) (be > bs).
+__device__ __forceinline__ int rep_block(int bs, int be, int rep_pos)
+{
+    return rep_pos == 1 ? bs : rep_pos == 2 ? be - 1 : bs + ((be - bs) >> 1);
+}
+
+constexpr uint32_t kKeyNegInf = 0x007fffffu;  // score_key(-inf): a real branch without admissible pair
 
 // rounded chunk bound round(j*Tb/kb), halves up, with Tb = a*kb + r split so that
 // everything fits 32-bit arithmetic (j, r <= 1024).

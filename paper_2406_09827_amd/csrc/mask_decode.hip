@@ -39,9 +39,11 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
     int32_t *out = p.idx_out + wg * kb;
 
-    const int Tb = kv_len > 0 ? (kv_len + BK - 1) / BK : 0;
+    // BK = key rows scored per block; with a key sampling stride the block itself is bk = BK * b_sk keys
+    const int bsk = p.b_sk, bk = BK * bsk;
+    const int Tb = kv_len > 0 ? (kv_len + bk - 1) / bk : 0;
     if (Tb <= kb) {
-        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j * BK : kSentinel;
+        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j * bk : kSentinel;
         return;
     }
 
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
                     const int mid = s + ((e - s) >> 1);
                     const int bs = (slot & 1) ? mid : s, be = (slot & 1) ? e : mid;
                     ok = be > bs;
-                    t = (bs + ((be - bs) >> 1)) * BK;
+                    if (ok) t = rep_block(bs, be, p.rep_pos) * bk;
                 }
                 t0[u] = ok ? t : -1;
                 pg[u] = page_of_row<PAGED>(p, b, ok ? t : 0);  // all page lookups of the stage first
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
                     // rows past the end of the sequence re-read its last row and are ignored below
-                    const int dn = t0[u] >= 0 ? min(n, kv_len - 1 - t) : 0;
+                    const int dn = t0[u] >= 0 ? min(n * bsk, kv_len - 1 - t) : 0;
                     const uint4 x = *(const uint4 *)(src + (int64_t)dn * p.ks_r);
                     const int q4 = 4 * (u * BK + n);
                     kv[q4] = x.x; kv[q4 + 1] = x.y; kv[q4 + 2] = x.z; kv[q4 + 3] = x.w;
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
                 for (int n = 0; n < BK; ++n) {
                     const int q4 = 4 * (u * BK + n);
                     const float dsum = row_group_sum<LPR>(dot8_bf16(qv, make_uint4(kv[q4], kv[q4 + 1], kv[q4 + 2], kv[q4 + 3])));
-                    if (t0[u] + n < kv_len) best = fmaxf(best, dsum);
+                    if (t0[u] + n * bsk < kv_len) best = fmaxf(best, dsum);
                 }
                 const int slot = base + u * RPW + grp;
                 if (lc == 0 && slot < NB) keys[slot] = t0[u] >= 0 ? score_key(best) : 0u;
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     }
 
     const int *ns = nds[wave][cur];
-    for (int j = lane; j < kb; j += 64) out[j] = ns[j] * BK;
+    for (int j = lane; j < kb; j += 64) out[j] = ns[j] * bk;
 }
 
 template <int BK, int D, int ROWS>
@@ -179,7 +181,8 @@ static hipError_t launch_e(const KParams &p, dim3 grid, hipStream_t st)
 
 bool mask_decode_supported(const KParams &p, bool bf16)
 {
-    return bf16 && p.q_len == 1 && p.bq == 1 && (p.bk == 1 || p.bk == 2 || p.bk == 4) && p.kb <= 512;
+    const int rows = p.bk / p.b_sk;  // key rows scored per block
+    return bf16 && p.q_len == 1 && p.bq == 1 && (rows == 1 || rows == 2 || rows == 4) && p.kb <= 512;
 }
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
@@ -187,13 +190,14 @@ hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
     const int64_t waves = (int64_t)p.batch * p.hq;
     if (waves == 0) return hipSuccess;
     dim3 grid((unsigned)((waves + 3) / 4));
+    const int rows = p.bk / p.b_sk;
     if (p.d == 64) {
-        if (p.bk == 1) return launch_e<1, 64>(p, grid, st);
-        if (p.bk == 2) return launch_e<2, 64>(p, grid, st);
+        if (rows == 1) return launch_e<1, 64>(p, grid, st);
+        if (rows == 2) return launch_e<2, 64>(p, grid, st);
         return launch_e<4, 64>(p, grid, st);
     }
-    if (p.bk == 1) return launch_e<1, 128>(p, grid, st);
-    if (p.bk == 2) return launch_e<2, 128>(p, grid, st);
+    if (rows == 1) return launch_e<1, 128>(p, grid, st);
+    if (rows == 2) return launch_e<2, 128>(p, grid, st);
     return launch_e<4, 128>(p, grid, st);
 }
 

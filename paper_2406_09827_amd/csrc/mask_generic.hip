@@ -64,7 +64,9 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
             if (j < kb) { s = nd_s[j]; e = nd_e[j]; mid = s + ((e - s) >> 1); }
             br_s[2 * j] = s; br_e[2 * j] = mid;
             br_s[2 * j + 1] = mid; br_e[2 * j + 1] = e;
-            keys[2 * j] = 0; keys[2 * j + 1] = 0;
+            // a real branch starts at "-inf" (it may end up without an admissible pair), an empty one at 0
+            keys[2 * j] = mid > s ? kKeyNegInf : 0u;
+            keys[2 * j + 1] = e > mid ? kKeyNegInf : 0u;
         }
         __syncthreads();
 
@@ -72,16 +74,17 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
         const int n_key_rows = 2 * kb * bk;
         for (int rr = grp; rr < n_key_rows; rr += kThreads / 16) {
             const int slot = rr / bk, n = rr - slot * bk;
+            if (n % p.b_sk) continue;  // key sampling stride
             const int s = br_s[slot], e = br_e[slot];
             if (e <= s) continue;
-            const int t = (s + ((e - s) >> 1)) * bk + n;  // key of the centre block
+            const int t = rep_block(s, e, p.rep_pos) * bk + n;  // key of the representative block
             if (t >= kv_len) continue;
             const T *krow = Kbase + kv_row_offset(p, b, hk, t) + l16 * CH;
             float kreg[CH];
 #pragma unroll
             for (int c = 0; c < CH; ++c) kreg[c] = ld_f32(krow + c);
             float best = -INFINITY;
-            for (int m = 0; m < n_rows; ++m) {
+            for (int m = 0; m < n_rows; m += p.b_sq) {  // row sampling stride
                 if (t > pos0 + m) continue;  // causal: key in the future of this row
                 const float *qrow = q_s + m * D + l16 * CH;
                 float acc = 0.f;

@@ -1,4 +1,4 @@
-// Instantiates the prefill mask-estimation kernels for key blocks of 1 token.
+// Instantiates the prefill mask-estimation kernels for 1 scored key row per block (bk / b_sk).
 #include "mask_mfma_impl.h"
 
 namespace hipattn {

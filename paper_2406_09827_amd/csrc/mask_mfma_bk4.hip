@@ -1,4 +1,4 @@
-// Instantiates the prefill mask-estimation kernels for key blocks of 4 tokens.
+// Instantiates the prefill mask-estimation kernels for 4 scored key rows per block (bk / b_sk).
 #include "mask_mfma_impl.h"
 
 namespace hipattn {

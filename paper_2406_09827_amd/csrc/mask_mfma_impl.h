@@ -15,6 +15,8 @@
 //     further tile ahead, so no LDS round trip sits between two tiles.  Rows of empty
 //     branches load row 0 of the sequence (always mapped) and drop the result: loads stay
 //     unconditional.
+//   * Sampling strides b_sq / b_sk (powers of two) shrink the operand tiles: only the sampled query
+//     rows are loaded into the A operand, only the sampled key rows of a block are gathered.
 //   * v_mfma_f32_32x32x16_bf16 gives a 32(query) x 32(key) score tile; the branch score is
 //     the max over the admissible query rows (in-lane, then lanes l and l+32) and over the
 //     bk keys of the block (neighbouring lanes, DPP).
@@ -41,13 +43,14 @@ __device__ __forceinline__ float max_half_swap(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// MT = 32-row query tiles (1 or 2), E = branch slots / 64, D = head dim, LB = log2(bk)
+// MT = 32-row query tiles (1 or 2), E = branch slots / 64, D = head dim,
+// LB = log2(key rows scored per block) = log2(bk / b_sk)
 template <int MT, int E, int D, bool PAGED, int LB>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
-    constexpr int BK = 1 << LB;
+    constexpr int BK = 1 << LB;    // key rows scored per representative block
     constexpr int CPR = D / 8;     // 16-byte chunks per key row
     constexpr int RPI = 64 / CPR;  // rows per wave-wide load
     constexpr int NLD = 32 / RPI;  // rows (= loads) per lane and tile
@@ -84,17 +87,22 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
     const int h = hk * p.g + (int)(o % p.g);
     const int kb = p.kb;
+    // sampling strides of the block score are powers of two here: key row n of a block is its key
+    // n << ks (ks = log2 b_sk), query row i of the operand is row i << qs of the block (qs = log2 b_sq)
+    const int ks = __builtin_ctz(p.b_sk), qs = __builtin_ctz(p.b_sq);
+    const int lbk = LB + ks;  // log2(bk)
 
     const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
     const int row0 = qb * p.bq;
     const int n_rows = min(p.bq, p.q_len - row0);
+    const int n_eff = (n_rows + p.b_sq - 1) >> qs;  // sampled query rows
     const int pos0 = kv_len - p.q_len + row0;
     const int L = min(kv_len, pos0 + n_rows);
     int32_t *out = p.idx_out + (((int64_t)b * p.hq + h) * p.nqb + qb) * kb;
 
-    const int Tb = L > 0 ? (L + BK - 1) >> LB : 0;
+    const int Tb = L > 0 ? (L + p.bk - 1) >> lbk : 0;
     if (Tb <= kb) {
-        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j << LB : kSentinel;
+        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j << lbk : kSentinel;
         return;
     }
 
@@ -108,7 +116,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (i < n_rows) v = *(const uint4 *)(Qb + (int64_t)i * p.qs_r + kk * 16 + hh * 8);
+                if (i < n_eff) v = *(const uint4 *)(Qb + (int64_t)(i << qs) * p.qs_r + kk * 16 + hh * 8);
                 qf[mt][kk] = __builtin_bit_cast(bf16x8, v);
             }
         }
@@ -123,8 +131,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // scoring loop only looks the representative up.
     auto put_branches = [&](int j, int s, int e) __attribute__((always_inline)) {
         const int mid = s + ((e - s) >> 1);
-        brt[2 * j] = mid > s ? (s + ((mid - s) >> 1)) << LB : -1;
-        brt[2 * j + 1] = (mid + ((e - mid) >> 1)) << LB;
+        brt[2 * j] = mid > s ? rep_block(s, mid, p.rep_pos) << lbk : -1;
+        brt[2 * j + 1] = rep_block(mid, e, p.rep_pos) << lbk;
     };
     for (int i = lane; i < NB; i += 64) { keys[i] = 0; brt[i] = -1; }
     wave_lds_sync();
@@ -140,7 +148,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     const int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
-    const bool full_rows = n_rows == 32 * MT;
+    const bool full_rows = n_eff == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
     // row 0 of this sequence / kv head (contiguous layout only)
     const char *Kseq = (const char *)(Kbase + (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h);
@@ -169,7 +177,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     auto load_rows = [&](int tile, const meta_t &mt_, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
         {
             const int sl = (tile * 32 + col) >> LB, tf = mt_.m[SPL];
-            const int tt = tf + (col & (BK - 1));
+            const int tt = tf + ((col & (BK - 1)) << ks);
             t = (tf >= 0 && tt < kv_len) ? tt : -1;
             slot = tf >= 0 ? sl : ~sl;
         }
@@ -184,14 +192,14 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                 const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
-                    const uint4 x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + n, last) - tf) * p.ks_r);
+                    const uint4 x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + (n << ks), last) - tf) * p.ks_r);
                     const int j = i * BK + n;
                     R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
                 }
             } else {
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
-                    const uint4 x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + n, last) * row_bytes + (uint32_t)lc * 16u));
+                    const uint4 x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + (n << ks), last) * row_bytes + (uint32_t)lc * 16u));
                     const int j = i * BK + n;
                     R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
                 }
@@ -227,7 +235,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             for (int mt = 0; mt < MT; ++mt)
                 acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv[kk]), acc[mt], 0, 0, 0);
         // max over the admissible query rows of this lane's key column
-        const int lo = t - pos0;  // rows i < lo would look into the future
+        const int lo = t - pos0;  // block rows below lo would look into the future
         float v = -INFINITY;
         if (full_rows && __ballot(lo > 0) == 0) {
 #pragma unroll
@@ -243,7 +251,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int i = mt * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-                    if (i >= lo && i < n_rows) v = fmaxf(v, acc[mt][r]);
+                    if ((i << qs) >= lo && i < n_eff) v = fmaxf(v, acc[mt][r]);
                 }
         }
         if (t < 0) v = -INFINITY;
@@ -324,7 +332,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         wave_lds_sync();
     }
 
-    for (int j = lane; j < kb; j += 64) out[j] = ns[j] << LB;
+    for (int j = lane; j < kb; j += 64) out[j] = ns[j] << lbk;
 }
 
 // One query tile: two waves per SIMD (register budget 256); two query tiles: one wave per SIMD.
@@ -370,7 +378,7 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     const int64_t units = groups * per_group;
     if (units == 0) return hipSuccess;
     dim3 grid((unsigned)((units + 3) / 4));
-    if (p.bq <= 32) return p.d == 64 ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st);
+    if ((p.bq + p.b_sq - 1) / p.b_sq <= 32) return p.d == 64 ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st);
     return p.d == 64 ? launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, st);
 }
 

@@ -189,3 +189,31 @@ def test_mask_reuse_across_decode_steps():
                            kv_lens=lens.cpu().numpy(), n_sink=n_sink, n_window=n_window, n_threads=8)
         ref = oracle.sparse_attn(p, hx["Q"], hx["K"], hx["V"], idx.cpu().numpy())
         U.check_output(out.float().cpu().numpy(), ref, "bf16")
+
+
+# ---- scoring variants of the mask estimation: sampling strides and representative position ------
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("bq,bk,b_sq,b_sk,rep_pos", [(32, 2, 2, 2, 0), (64, 4, 2, 1, 0), (32, 8, 1, 2, 1), (32, 4, 4, 4, 2),
+                                                     (16, 2, 1, 1, 1), (48, 2, 2, 1, 2)])
+def test_prefill_scoring_variants(flags, bq, bk, b_sq, b_sk, rep_pos):
+    for integer in (True, False):
+        w = synth.Workload("variants", 1, 4, 2, 128, 2500, 2500, 64 * bk, bq, bk, "bf16", rho=0.95, spike_every=512,
+                           integer=integer, seed=66)
+        nqb = w.n_query_blocks
+        units = [(0, h, qb) for h in range(4) for qb in sorted({0, 3, 4, 5, 9, nqb // 2, nqb - 2, nqb - 1})]
+        U.run_case(w, flags, units=units, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
+
+
+def test_fp32_scoring_variants():
+    U.run_case(synth.C1_INT, 0, b_sq=4, b_sk=2, rep_pos=2)
+    U.run_case(synth.C1, 0, b_sq=2, b_sk=1, rep_pos=1)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("bk,b_sk,rep_pos,paged", [(2, 2, 0, False), (4, 2, 1, True), (8, 2, 2, False), (4, 4, 0, True), (2, 1, 2, True)])
+def test_decode_scoring_variants(flags, bk, b_sk, rep_pos, paged):
+    for integer in (True, False):
+        w = synth.Workload("variants_dec", 6, 8, 2, 128, 1, 9000, 128 * bk, 1, bk, "bf16", rho=0.9, ragged=(300, 9000),
+                           page_size=16 if paged else 0, integer=integer, seed=67)
+        U.run_case(w, flags, b_sk=b_sk, rep_pos=rep_pos)
