@@ -61,6 +61,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][NB / 2], nde[4][NB / 2];                   // node ranges [s, e) in key blocks
     __shared__ __attribute__((aligned(16))) int brt_s[4][NB];        // per branch slot: first key of its centre block, -1 = empty
+    __shared__ int fsl_s[4][NB / 2];                                 // final round: slot of the i-th block still to be scored
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -123,7 +124,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     }
 
     uint32_t *keys = keys_s[wave];
-    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave];
+    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave], *fsl = fsl_s[wave];
     char *tile_s = (char *)tile_buf[wave];
 
     // the two branches of node [s, e): left [s, mid) (empty for a one-block node), right [mid, e);
@@ -147,7 +148,13 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     wave_lds_sync();
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
-    const int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
+    int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
+    // Final round with the centre representative: every node is one or two blocks long.  A
+    // one-block node IS its representative and the right half of a two-block node is the
+    // node's representative, so their scores are carried over from the round that kept the
+    // node; only the left halves of two-block nodes are scored.  In that round the branch table
+    // is a compact list of those blocks and fsl[] names the slot each one belongs to.
+    bool final_mode = false;
     const bool full_rows = n_eff == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
     // row 0 of this sequence / kv head (contiguous layout only)
@@ -156,7 +163,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 
     // Branch-table entries one tile needs: m[0..SPL-1] for the rows this lane LOADS, m[SPL] for
     // the row it SCORES (row col of the tile).
-    struct meta_t { int m[SPL + 1]; };
+    struct meta_t { int m[SPL + 1]; int sl; };
     auto read_meta = [&](int tile, meta_t &mt_) __attribute__((always_inline)) {
         const int *src = brt + tile * (32 >> LB) + lg * SPL;
         if (SPL == 1) mt_.m[0] = src[0];
@@ -169,6 +176,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             }
         }
         mt_.m[SPL] = brt[(tile * 32 + col) >> LB];
+        const int ti = (tile * 32 + col) >> LB;
+        mt_.sl = final_mode ? fsl[min(ti, NB / 2 - 1)] : ti;  // (entries past the list are never used)
     };
 
     // Coalesced loads of a tile's 32 rows from the metadata read earlier.
@@ -176,10 +185,12 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // slot = its branch slot, complemented when the branch is empty.
     auto load_rows = [&](int tile, const meta_t &mt_, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
         {
-            const int sl = (tile * 32 + col) >> LB, tf = mt_.m[SPL];
+            const int sl = mt_.sl, tf = mt_.m[SPL];
             const int tt = tf + ((col & (BK - 1)) << ks);
             t = (tf >= 0 && tt < kv_len) ? tt : -1;
-            slot = tf >= 0 ? sl : ~sl;
+            // empty: in a normal round the slot is still named (complemented) so its key gets cleared;
+            // in the final round an entry past the end of the list names no slot at all
+            slot = tf >= 0 ? sl : (final_mode ? -1 : ~sl);
         }
         // per branch slot: offset of the block's first row; rows past the end of the sequence
         // re-read its last row (their score is dropped: t < 0 above)
@@ -259,7 +270,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         if (LB >= 1) v = fmaxf(v, dpp_f<0xB1>(v));  // lane ^ 1
         if (LB >= 2) v = fmaxf(v, dpp_f<0x4E>(v));  // lane ^ 2
         const int sl = slot < 0 ? ~slot : slot;
-        if (hh == 0 && (col & (BK - 1)) == 0) keys[sl] = slot < 0 ? 0u : score_key(v);
+        // (in the final round the keys are preset and an empty entry names no slot)
+        if (hh == 0 && (col & (BK - 1)) == 0 && (slot >= 0 || !final_mode)) keys[sl] = slot < 0 ? 0u : score_key(v);
     };
 
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
@@ -320,14 +332,44 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                 ce[i] = (slot & 1) ? e : mid;
             }
         }
+        const bool next_is_final = ((maxlen + 1) >> 1) == 2 && p.rep_pos == 0;
+        if (next_is_final) {
+            // the branch table becomes the compact list of blocks still to be scored
+            for (int i = lane; i < 2 * kb; i += 64) brt[i] = -1;
+        }
         wave_lds_sync();
+        if (!next_is_final) {
 #pragma unroll
-        for (int i = 0; i < E; ++i) {
-            if (keep[i]) {
-                ns[dest[i]] = cs[i];
-                ne[dest[i]] = ce[i];
-                put_branches(dest[i], cs[i], ce[i]);
+            for (int i = 0; i < E; ++i) {
+                if (keep[i]) {
+                    ns[dest[i]] = cs[i];
+                    ne[dest[i]] = ce[i];
+                    put_branches(dest[i], cs[i], ce[i]);
+                }
             }
+        } else {
+            int n_todo = 0;
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+                const bool two = keep[i] && ce[i] - cs[i] == 2;
+                const uint64_t b2 = __ballot(two);
+                if (keep[i]) {
+                    const int d = dest[i];
+                    ns[d] = cs[i];
+                    ne[d] = ce[i];
+                    keys[2 * d] = 0u;           // left half: empty, or scored below
+                    keys[2 * d + 1] = key[i];   // right half / the node itself: score carried over
+                    if (two) {
+                        const int ti = n_todo + lane_prefix_count(b2);
+                        brt[ti] = cs[i] << lbk;
+                        fsl[ti] = 2 * d;
+                    }
+                }
+                n_todo += __popcll(b2);
+            }
+            for (int i = 2 * kb + lane; i < NB; i += 64) keys[i] = 0u;
+            final_mode = true;
+            n_tiles = (n_todo * BK + 31) >> 5;
         }
         wave_lds_sync();
     }
