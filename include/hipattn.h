@@ -139,6 +139,11 @@ size_t hip_workspace_bytes(const hip_problem *p);
 /* Static, human-readable text for a return code. */
 const char *hip_strerror(int code);
 
+/* Test aid, not part of the method: fills the LDS of every compute unit with `pattern` (one
+ * kernel on `stream`), so that a kernel that wrongly reads LDS it never wrote sees that value
+ * instead of whatever an earlier kernel left there.  The GPU tests call it before every call. */
+int hip_attn_poison_lds(uint32_t pattern, void *stream);
+
 /* Library version, major*100 + minor. */
 int hip_attn_version(void);
 

@@ -18,7 +18,8 @@ SENTINEL = 2**31 - 1
 F32, BF16 = 0, 1
 FORCE_GENERIC = 1
 
-EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
+EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version",
+           "hip_attn_poison_lds")
 
 
 class HipProblem(ctypes.Structure):
@@ -58,6 +59,8 @@ def load() -> ctypes.CDLL:
         lib.hip_strerror.restype = ctypes.c_char_p
         lib.hip_strerror.argtypes = [ctypes.c_int]
         lib.hip_attn_version.restype = ctypes.c_int
+        lib.hip_attn_poison_lds.restype = ctypes.c_int
+        lib.hip_attn_poison_lds.argtypes = [ctypes.c_uint32, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -116,6 +119,13 @@ def make_problem(Q: torch.Tensor, K: torch.Tensor, k: int, bq: int, bk: int,
 
 def _stream(t: torch.Tensor) -> int:
     return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def poison_lds(pattern: int = 0xAAAAAAAA) -> None:
+    """Test aid: overwrite the LDS of every compute unit (see include/hipattn.h)."""
+    rc = load().hip_attn_poison_lds(pattern, torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise HipAttnError(rc)
 
 
 def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,

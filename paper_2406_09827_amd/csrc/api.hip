@@ -64,6 +64,13 @@ int prepare(const hip_problem *hp, KParams &kp)
     return HIP_ATTN_OK;
 }
 
+__global__ __launch_bounds__(kThreads) void poison_lds_kernel(uint32_t pattern)
+{
+    extern __shared__ uint32_t lds_words[];
+    volatile uint32_t *w = lds_words;  // volatile: the stores are the whole point
+    for (int i = threadIdx.x; i < 65536 / 4; i += kThreads) w[i] = pattern;
+}
+
 int launch_result(hipError_t e) { return e == hipSuccess ? HIP_ATTN_OK : HIP_ATTN_ELAUNCH - (int)e; }
 
 }  // namespace
@@ -123,6 +130,13 @@ const char *hip_strerror(int code)
     }
 }
 
-int hip_attn_version(void) { return 100; }
+int hip_attn_poison_lds(uint32_t pattern, void *stream)
+{
+    // 2 workgroups of 64 KB fit a compute unit: 8192 workgroups sweep all 256 units many times
+    hipLaunchKernelGGL(poison_lds_kernel, dim3(8192), dim3(kThreads), 65536, static_cast<hipStream_t>(stream), pattern);
+    return launch_result(hipGetLastError());
+}
+
+int hip_attn_version(void) { return 101; }
 
 }  // extern "C"

@@ -29,12 +29,14 @@ def _max_len(w, x):
 
 
 def gpu_mask(w, x, flags=0, b_sq=1, b_sk=1, rep_pos=0):
+    hipattn.poison_lds(0xAAAAAAAA)   # a kernel reading LDS it never wrote now sees a fixed, hostile value
     return hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                      page_table=x["page_table"], max_kv_len=_max_len(w, x), flags=flags,
                                      b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
 
 
 def gpu_attn(w, x, idx, flags=0, sm_scale=0.0, n_sink=0, n_window=0):
+    hipattn.poison_lds(0x7FC0FFEE)
     return hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                    page_table=x["page_table"], max_kv_len=_max_len(w, x), sm_scale=sm_scale, flags=flags,
                                    n_sink=n_sink, n_window=n_window)
