@@ -213,23 +213,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const bool ok = tkey[e] >= lo && tkey[e] < hi;
-                        s[4 * g + e] = ok ? sacc[4 * g + e] * c : -INFINITY;
+                        s[4 * g + e] = ok ? sacc[4 * g + e] : -INFINITY;
                     }
                 }
             } else {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = sacc[r] * c;
+                for (int r = 0; r < 16; ++r) s[r] = sacc[r];
             }
+            // raw scores here; the scale (c > 0) is applied to the maximum and inside the exponent
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
             const float m_new = fmaxf(m_run, mx);
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
             float lsum = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                s[r] = __builtin_amdgcn_exp2f(s[r] - m_safe);
+                s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, -m_safe));
                 lsum += s[r];
             }
             l_run = l_run * alpha + lsum;
@@ -266,16 +267,21 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 const bf16_t *src0 = vt + (4 * hh + (i16 >> 2)) * PITCH + cb * 16 + (i16 & 3) * 4;
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
+                    bf16x8 va[CT];
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) {
                         // keys 16st + 4hh + {0..3} and 16st + 8 + 4hh + {0..3}, channel ct*32 + col
                         const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src0 + (16 * st) * PITCH + ct * 32));
                         const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src0 + (16 * st + 8) * PITCH + ct * 32));
                         const uint2 a = __builtin_bit_cast(uint2, lo4), c2 = __builtin_bit_cast(uint2, hi4);
-                        const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, c2.x, c2.y));
-                        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[ct], 0, 0, 0);
-                        oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pl[st], oacc[ct], 0, 0, 0);
+                        va[ct] = __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, c2.x, c2.y));
                     }
+                    // the CT accumulators are independent: interleave them so that no multiply waits
+                    // for the one before it
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ct], pb[st], oacc[ct], 0, 0, 0);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ct], pl[st], oacc[ct], 0, 0, 0);
                 }
             }
         }
