@@ -19,20 +19,40 @@
 
 namespace hipattn {
 
-template <int E, int BK, int D, int ROWS, bool PAGED>
-__global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
+// SPLIT = false: one wave per (sequence, head), four independent problems per workgroup.
+// SPLIT = true : one workgroup per (sequence, head); the four waves score a quarter of the
+//                branches each (stage i goes to wave i % 4), meet at a barrier, run the selection
+//                redundantly and write a quarter of the survivors each.  Used at small batch,
+//                where one wave per SIMD cannot keep enough loads in flight.
+template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xcd_map)
 {
     constexpr int NB = 64 * E;
     constexpr int LPR = D / 8;        // lanes per key row
     constexpr int RPW = 64 / LPR;     // rows (= branches) per wave-wide load
     constexpr int U = ROWS / BK;      // branches per lane group and stage: ROWS row loads per lane, two stages in flight
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
-    __shared__ uint32_t keys_s[4][NB];
-    __shared__ int nds[4][2][NB / 2], nde[4][2][NB / 2];
+    constexpr int NW = SPLIT ? 1 : 4;  // private copies of the per-problem LDS state
+    constexpr int WS = SPLIT ? 4 : 1;  // waves sharing one problem
+    __shared__ uint32_t keys_s[NW][NB];
+    __shared__ int nds[NW][2][NB / 2], nde[NW][2][NB / 2];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, lc = lane % LPR;
-    const int64_t wg = (int64_t)blockIdx.x * 4 + wave;
+    const int own = SPLIT ? 0 : wave;  // which LDS copy
+    int64_t wg;
+    if (SPLIT) {
+        // keep the query heads of a KV group on one XCD (blockIdx.x % 8), next to each other in time
+        const int64_t bid = blockIdx.x;
+        if (xcd_map) {
+            const int64_t seq = bid >> 3, gi = (bid & 7) + 8 * (seq / p.g);
+            wg = gi * p.g + seq % p.g;  // = (b * hkv + hk) * g + head in group = b * hq + h
+        } else {
+            wg = bid;
+        }
+    } else {
+        wg = (int64_t)blockIdx.x * 4 + wave;
+    }
     if (wg >= (int64_t)p.batch * p.hq) return;
     const int b = (int)(wg / p.hq), h = (int)(wg % p.hq), hk = h / p.g;
     const int kb = p.kb;
@@ -43,26 +63,31 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
     const int bsk = p.b_sk, bk = BK * bsk;
     const int Tb = kv_len > 0 ? (kv_len + bk - 1) / bk : 0;
     if (Tb <= kb) {
-        for (int j = lane; j < kb; j += 64) out[j] = j < Tb ? j * bk : kSentinel;
+        for (int j = SPLIT ? (int)threadIdx.x : lane; j < kb; j += SPLIT ? kThreads : 64) out[j] = j < Tb ? j * bk : kSentinel;
         return;
     }
+    // all waves of a problem hold identical copies of its state when SPLIT
+    auto sync_problem = [&]() __attribute__((always_inline)) {
+        if (SPLIT) __syncthreads(); else wave_lds_sync();
+    };
+    const int tix = SPLIT ? (int)threadIdx.x : lane, tn = SPLIT ? kThreads : 64;
 
     const uint4 qv = *(const uint4 *)((const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + lc * 8);
-    uint32_t *keys = keys_s[wave];
-    for (int i = lane; i < NB; i += 64) keys[i] = 0;
+    uint32_t *keys = keys_s[own];
+    for (int i = tix; i < NB; i += tn) keys[i] = 0;
     {
         const int a = Tb / kb, r = Tb % kb;
-        for (int j = lane; j < kb; j += 64) {
-            nds[wave][0][j] = chunk_bound(j, a, r, kb);
-            nde[wave][0][j] = chunk_bound(j + 1, a, r, kb);
+        for (int j = tix; j < kb; j += tn) {
+            nds[own][0][j] = chunk_bound(j, a, r, kb);
+            nde[own][0][j] = chunk_bound(j + 1, a, r, kb);
         }
     }
-    wave_lds_sync();
+    sync_problem();
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     int cur = 0;
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
-        const int *ns = nds[wave][cur], *ne = nde[wave][cur];
+        const int *ns = nds[own][cur], *ne = nde[own][cur];
 
         // one stage = U branches per lane group: node lookup, then the (unconditional) loads of
         // the representative block's BK rows.  t0 < 0 marks an empty branch.
@@ -112,20 +137,22 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
             }
         };
 
-        constexpr int STEP = RPW * U;
+        constexpr int STEP = RPW * U;   // branches per stage
+        constexpr int STRIDE = WS * STEP;  // distance between two stages of the same wave
         stage_t ka, kbuf;
         int ta[U], tb[U];
-        fetch(0, ka, ta);
-        for (int base = 0; base < 2 * kb; base += 2 * STEP) {
-            const bool has_b = base + STEP < 2 * kb;
-            if (has_b) fetch(base + STEP, kbuf, tb);
+        const int first = SPLIT ? wave * STEP : 0;
+        if (first < 2 * kb) fetch(first, ka, ta);
+        for (int base = first; base < 2 * kb; base += 2 * STRIDE) {
+            const bool has_b = base + STRIDE < 2 * kb;
+            if (has_b) fetch(base + STRIDE, kbuf, tb);
             score(base, ka, ta);
             if (has_b) {
-                if (base + 2 * STEP < 2 * kb) fetch(base + 2 * STEP, ka, ta);
-                score(base + STEP, kbuf, tb);
+                if (base + 2 * STRIDE < 2 * kb) fetch(base + 2 * STRIDE, ka, ta);
+                score(base + STRIDE, kbuf, tb);
             }
         }
-        wave_lds_sync();
+        sync_problem();
 
         uint32_t key[E];
         bool keep[E];
@@ -133,10 +160,10 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
 #pragma unroll
         for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
         select_topk_ordered<E>(key, kb, keep, dest);
-        int *ns2 = nds[wave][cur ^ 1], *ne2 = nde[wave][cur ^ 1];
+        int *ns2 = nds[own][cur ^ 1], *ne2 = nde[own][cur ^ 1];
 #pragma unroll
         for (int i = 0; i < E; ++i) {
-            if (keep[i]) {
+            if (keep[i] && (!SPLIT || (i & 3) == wave)) {
                 const int slot = i * 64 + lane, node = slot >> 1;
                 const int s = ns[node], e = ne[node];
                 const int mid = s + ((e - s) >> 1);
@@ -145,21 +172,21 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p)
             }
         }
         cur ^= 1;
-        wave_lds_sync();
+        sync_problem();
     }
 
-    const int *ns = nds[wave][cur];
-    for (int j = lane; j < kb; j += 64) out[j] = ns[j] * bk;
+    const int *ns = nds[own][cur];
+    for (int j = tix; j < kb; j += tn) out[j] = ns[j] * bk;
 }
 
-template <int BK, int D, int ROWS>
-static hipError_t launch_r(const KParams &p, dim3 grid, hipStream_t st)
+template <int BK, int D, int ROWS, bool SPLIT>
+static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t st)
 {
     dim3 block(kThreads);
 #define HIPATTN_LAUNCH(EV)                                                                                  \
     do {                                                                                                    \
-        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true>), grid, block, 0, st, p);  \
-        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false>), grid, block, 0, st, p);       \
+        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true, SPLIT>), grid, block, 0, st, p, xcd_map);  \
+        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false, SPLIT>), grid, block, 0, st, p, xcd_map);       \
     } while (0)
     if (p.kb <= 128) HIPATTN_LAUNCH(4);
     else if (p.kb <= 256) HIPATTN_LAUNCH(8);
@@ -168,15 +195,22 @@ static hipError_t launch_r(const KParams &p, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
-// Few waves (small batch): each wave is alone on its SIMD and has to keep the memory pipeline
-// full by itself -> deep stages.  Many waves: shallower stages need fewer registers, so more
-// waves fit a SIMD and hide each other's latency (including the page-table lookups).
+// Few problems (small batch): a workgroup per (sequence, head), four waves sharing the scoring, so
+// that enough loads are in flight per compute unit.  Many problems: a wave per problem; shallower
+// stages need fewer registers, so more waves fit a SIMD and hide each other's latency (including the
+// page-table lookups).
 template <int BK, int D>
-static hipError_t launch_e(const KParams &p, dim3 grid, hipStream_t st)
+static hipError_t launch_e(const KParams &p, hipStream_t st)
 {
-    const int64_t waves = (int64_t)p.batch * p.hq;
-    if (waves >= 4096) return launch_r<BK, D, 8>(p, grid, st);
-    return launch_r<BK, D, 16>(p, grid, st);
+    const int64_t problems = (int64_t)p.batch * p.hq;
+    if (problems < 2048) {
+        const int64_t groups = (int64_t)p.batch * p.hkv;
+        const int xcd_map = groups % 8 == 0 ? 1 : 0;
+        return launch_r<BK, D, 8, true>(p, dim3((unsigned)problems), xcd_map, st);
+    }
+    dim3 grid((unsigned)((problems + 3) / 4));
+    if (problems >= 4096) return launch_r<BK, D, 8, false>(p, grid, 0, st);
+    return launch_r<BK, D, 16, false>(p, grid, 0, st);
 }
 
 bool mask_decode_supported(const KParams &p, bool bf16)
@@ -187,18 +221,16 @@ bool mask_decode_supported(const KParams &p, bool bf16)
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
 {
-    const int64_t waves = (int64_t)p.batch * p.hq;
-    if (waves == 0) return hipSuccess;
-    dim3 grid((unsigned)((waves + 3) / 4));
+    if ((int64_t)p.batch * p.hq == 0) return hipSuccess;
     const int rows = p.bk / p.b_sk;
     if (p.d == 64) {
-        if (rows == 1) return launch_e<1, 64>(p, grid, st);
-        if (rows == 2) return launch_e<2, 64>(p, grid, st);
-        return launch_e<4, 64>(p, grid, st);
+        if (rows == 1) return launch_e<1, 64>(p, st);
+        if (rows == 2) return launch_e<2, 64>(p, st);
+        return launch_e<4, 64>(p, st);
     }
-    if (rows == 1) return launch_e<1, 128>(p, grid, st);
-    if (rows == 2) return launch_e<2, 128>(p, grid, st);
-    return launch_e<4, 128>(p, grid, st);
+    if (rows == 1) return launch_e<1, 128>(p, st);
+    if (rows == 2) return launch_e<2, 128>(p, st);
+    return launch_e<4, 128>(p, st);
 }
 
 }  // namespace hipattn
