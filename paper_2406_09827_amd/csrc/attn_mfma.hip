@@ -108,6 +108,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     }
 
     const bf16_t *Kbase = (const bf16_t *)p.K, *Vbase = (const bf16_t *)p.V;
+    const int64_t seq_off = (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h;  // contiguous layout: row 0 of this slice
     bf16_t *vt = vt_s[wave];
     char *kt = (char *)kt_s[wave];
     uint32_t *mo = mo_s[wave];
@@ -147,10 +148,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         }
         {
             const int tr = t_c >= 0 ? t_c : 0;
-            const int64_t eo = row_offset_in<PAGED>(p, b, hk, tr, page_of_row<PAGED>(p, b, tr));
+            // what a loading lane needs to find the row: the page (paged pool) or the row's offset
+            // from the start of this sequence / kv head slice in 16-byte units (contiguous)
+            const uint32_t m = PAGED ? (uint32_t)page_of_row<true>(p, b, tr)
+                                     : (uint32_t)(((int64_t)tr * p.ks_r) >> 3);
             if (hh == 0) {
                 tk[col] = t_c;
-                mo[col] = (uint32_t)(eo >> 3);
+                mo[col] = m;
             }
         }
         wave_lds_sync();
@@ -160,10 +164,24 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             const uint4 m4 = *(const uint4 *)(mo + lg * NLD + j);
             off[j] = m4.x; off[j + 1] = m4.y; off[j + 2] = m4.z; off[j + 3] = m4.w;
         }
+        int tkl[NLD];  // positions of this lane's rows (paged variant: the offset inside the page)
+        if (PAGED) {
+#pragma unroll
+            for (int j = 0; j < NLD; j += 4) {
+                const int4 t4 = *(const int4 *)(tk + lg * NLD + j);
+                tkl[j] = t4.x; tkl[j + 1] = t4.y; tkl[j + 2] = t4.z; tkl[j + 3] = t4.w;
+            }
+        }
         wave_lds_sync();
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
-            const int64_t eo = ((int64_t)off[j] << 3) + lc * 8;
+            int64_t eo;
+            if (PAGED) {
+                const int tr = max(tkl[j], 0);
+                eo = row_offset_in<true>(p, b, hk, tr, (int)off[j]) + lc * 8;
+            } else {
+                eo = seq_off + ((int64_t)off[j] << 3) + lc * 8;
+            }
             const uint4 x = *(const uint4 *)(Kbase + eo);
             const uint4 y = *(const uint4 *)(Vbase + eo);
             RK[4 * j] = x.x; RK[4 * j + 1] = x.y; RK[4 * j + 2] = x.z; RK[4 * j + 3] = x.w;
@@ -311,7 +329,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 
 bool attn_mfma_supported(const KParams &p, bool bf16)
 {
-    return bf16 && p.q_len > 1 && p.bk <= 16 && (p.bk & (p.bk - 1)) == 0 && p.bq <= 64;
+    // contiguous variant: a row's offset inside its (sequence, kv head) slice is kept in 32 bits of 16-byte units
+    const bool fits = p.page_table || (int64_t)p.max_kv_len * p.ks_r < (1LL << 35);
+    return bf16 && p.q_len > 1 && p.bk <= 16 && (p.bk & (p.bk - 1)) == 0 && p.bq <= 64 && fits;
 }
 
 hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
