@@ -12,7 +12,10 @@
 
 namespace hipattn {
 
-template <int BK, int D, int ROWS, bool PAGED>
+// SPLIT = false: one wave per (sequence, head).  SPLIT = true (small batch): one workgroup per
+// (sequence, head), stage i of the block list goes to wave i % 4, the four partial softmax states
+// are merged through LDS.
+template <int BK, int D, int ROWS, bool PAGED, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 {
     constexpr int LPR = D / 8, RPW = 64 / LPR;
@@ -20,7 +23,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = lane / LPR, lc = lane % LPR;
-    const int64_t wg = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t wg = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
     if (wg >= (int64_t)p.batch * p.hq) return;
     const int b = (int)(wg / p.hq), h = (int)(wg % p.hq), hk = h / p.g;
     const int kb = p.kb;
@@ -124,16 +127,18 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
         m_run = m_new;
     };
 
-    constexpr int STEP = RPW * U;
+    constexpr int STEP = RPW * U;                      // blocks per stage
+    constexpr int STRIDE = (SPLIT ? 4 : 1) * STEP;     // distance between two stages of the same wave
     stage_t ka, va, kb2, vb2;
     int fa[U], fb[U];
-    fetch(0, ka, va, fa);
-    for (int base = 0; base < n_blocks; base += 2 * STEP) {
-        const bool has_b = base + STEP < n_blocks;
-        if (has_b) fetch(base + STEP, kb2, vb2, fb);
+    const int first_base = SPLIT ? wave * STEP : 0;
+    if (first_base < n_blocks) fetch(first_base, ka, va, fa);
+    for (int base = first_base; base < n_blocks; base += 2 * STRIDE) {
+        const bool has_b = base + STRIDE < n_blocks;
+        if (has_b) fetch(base + STRIDE, kb2, vb2, fb);
         consume(ka, va, fa);
         if (has_b) {
-            if (base + 2 * STEP < n_blocks) fetch(base + 2 * STEP, ka, va, fa);
+            if (base + 2 * STRIDE < n_blocks) fetch(base + 2 * STRIDE, ka, va, fa);
             consume(kb2, vb2, fb);
         }
     }
@@ -149,6 +154,31 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off, 64) * ao;
         m_run = m_new;
+    }
+    if (SPLIT) {
+        // lanes of group 0 of every wave hold that wave's state for channels lc*8 .. +8
+        __shared__ float part_s[4][LPR][10];
+        if (grp == 0) {
+            part_s[wave][lc][0] = m_run;
+            part_s[wave][lc][1] = l_run;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part_s[wave][lc][2 + i] = acc[i];
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        if (grp == 0) {
+#pragma unroll
+            for (int w = 1; w < 4; ++w) {
+                const float m_o = part_s[w][lc][0], l_o = part_s[w][lc][1];
+                const float m_new = fmaxf(m_run, m_o);
+                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                const float a = __builtin_amdgcn_exp2f(m_run - m_safe), ao = __builtin_amdgcn_exp2f(m_o - m_safe);
+                l_run = l_run * a + l_o * ao;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + part_s[w][lc][2 + i] * ao;
+                m_run = m_new;
+            }
+        }
     }
     if (grp == 0) {
         const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
@@ -171,15 +201,19 @@ hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
 {
     const int64_t waves = (int64_t)p.batch * p.hq;
     if (waves == 0) return hipSuccess;
-    dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
-    // deep stages when a wave is alone on its SIMD, shallow ones (more waves per SIMD) at large batch
+    // small batch: a workgroup per problem (four waves share its blocks); else a wave per problem,
+    // with deep stages when few waves share a SIMD and shallow ones (more waves per SIMD) at large batch
+    const bool split = waves < 2048;
+    dim3 grid((unsigned)(split ? waves : (waves + 3) / 4)), block(kThreads);
     const bool deep = waves < 4096, paged = p.page_table != nullptr;
 #define HIPATTN_LAUNCH(BKV, DV)                                                                        \
     do {                                                                                               \
-        if (deep && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, true>), grid, block, 0, st, p);        \
-        else if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, false>), grid, block, 0, st, p);           \
-        else if (paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true>), grid, block, 0, st, p);           \
-        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false>), grid, block, 0, st, p);                     \
+        if (split && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, true>), grid, block, 0, st, p);         \
+        else if (split) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, true>), grid, block, 0, st, p);            \
+        else if (deep && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, true, false>), grid, block, 0, st, p);    \
+        else if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, false, false>), grid, block, 0, st, p);            \
+        else if (paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, false>), grid, block, 0, st, p);            \
+        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, false>), grid, block, 0, st, p);                      \
     } while (0)
     if (p.d == 64) {
         if (p.bk == 1) HIPATTN_LAUNCH(1, 64);
