@@ -228,8 +228,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         }
     };
 
-    auto score = [&](int t, int slot) __attribute__((always_inline)) {
-        f32x16 acc[MT];
+    struct acc_t { f32x16 a[MT]; };
+    // first half of scoring a tile: operand reads and the multiplies (they run on in the matrix pipe
+    // while the wave goes on with the next tile's LDS writes and loads)
+    auto score_issue = [&](acc_t &A) __attribute__((always_inline)) {
+        f32x16 (&acc)[MT] = A.a;
 #pragma unroll
         for (int a = 0; a < MT; ++a)
 #pragma unroll
@@ -245,6 +248,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
                 acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv[kk]), acc[mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // second half: branch score from the product tile, written as an ordered key
+    auto score_finish = [&](const acc_t &A, int t, int slot) __attribute__((always_inline)) {
+        const f32x16 (&acc)[MT] = A.a;
         // max over the admissible query rows of this lane's key column
         const int lo = t - pos0;  // block rows below lo would look into the future
         float v = -INFINITY;
@@ -287,28 +295,45 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             load_rows(1, m1, R1, t1, s1);
             if (n_tiles > 3) read_meta(3, m1);
         }
+        // tile 0 goes into the LDS tile; from then on the tile after the one being multiplied is
+        // written to LDS (and the loads of the tile three ahead are issued) while the multiplies run
+        int tcur = t0, scur = s0;
+        park(R0);
+        if (2 < n_tiles) {
+            load_rows(2, m0, R0, t0, s0);
+            if (4 < n_tiles) read_meta(4, m0);
+        }
+        wave_lds_sync();
         for (int tile = 0; tile < n_tiles; tile += 2) {
-            {
-                const int tc = t0, sc = s0;
-                park(R0);
-                if (tile + 2 < n_tiles) {
-                    load_rows(tile + 2, m0, R0, t0, s0);
-                    if (tile + 4 < n_tiles) read_meta(tile + 4, m0);
-                }
-                wave_lds_sync();
-                score(tc, sc);
-                wave_lds_sync();
-            }
+            // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2
+            acc_t A;
+            score_issue(A);
+            int tn = -1, sn = -1;
             if (tile + 1 < n_tiles) {
-                const int tc = t1, sc = s1;
+                tn = t1; sn = s1;
                 park(R1);
                 if (tile + 3 < n_tiles) {
                     load_rows(tile + 3, m1, R1, t1, s1);
                     if (tile + 5 < n_tiles) read_meta(tile + 5, m1);
                 }
+            }
+            wave_lds_sync();
+            score_finish(A, tcur, scur);
+            if (tile + 1 < n_tiles) {
+                // tile+1 is in LDS, R0 holds tile+2, R1 tile+3
+                acc_t B;
+                score_issue(B);
+                tcur = -1; scur = -1;
+                if (tile + 2 < n_tiles) {
+                    tcur = t0; scur = s0;
+                    park(R0);
+                    if (tile + 4 < n_tiles) {
+                        load_rows(tile + 4, m0, R0, t0, s0);
+                        if (tile + 6 < n_tiles) read_meta(tile + 6, m0);
+                    }
+                }
                 wave_lds_sync();
-                score(tc, sc);
-                wave_lds_sync();
+                score_finish(B, tn, sn);
             }
         }
 
