@@ -85,7 +85,7 @@ def read_traffic(name: str):
         return None
 
 
-def cpu_baseline(w, x, budget_s: float):
+def cpu_baseline(w, x, budget_s: float, **variant):
     """The CPU oracle timed on a bounded random sample of (head, query block) units of the same
     workload (mask estimation + sparse attention), all host cores via OpenMP."""
     import numpy as np
@@ -93,7 +93,7 @@ def cpu_baseline(w, x, budget_s: float):
     from tests.gpu_util import oracle_problem, host
 
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 10**6))
-    p = oracle_problem(w, x, n_threads=cores)
+    p = oracle_problem(w, x, n_threads=cores, **variant)
     hx = host(x)
     rng = np.random.default_rng(1234)
     all_u = oracle.all_units(p)
@@ -129,6 +129,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--b-sq", type=int, default=1, help="query-row sampling stride of the block score (default: all rows)")
     ap.add_argument("--b-sk", type=int, default=1, help="key sampling stride of the block score (default: all keys)")
+    ap.add_argument("--top-r", type=int, default=0,
+                    help="score over each query row's top-r channels only (default 0: all channels; generic kernel)")
     ap.add_argument("--n-sink", type=int, default=0, help="sink keys added in the sparse attention (default 0)")
     ap.add_argument("--n-window", type=int, default=0, help="sliding-window keys added in the sparse attention (default 0)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -155,9 +157,13 @@ def main():
     idx = torch.empty((w.batch, w.n_q_heads, w.n_query_blocks, w.kb), dtype=torch.int32, device="cuda")
     out = torch.empty_like(x["Q"])
 
+    # scratch of the top-r pre-pass (a copy of Q), allocated once outside the timed region
+    ws = torch.empty(x["Q"].numel() * x["Q"].element_size(), dtype=torch.uint8, device="cuda") if args.top_r else None
+
     def step():
         hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk)
+                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
+                                  top_r=args.top_r, workspace=ws)
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
                                 n_sink=args.n_sink, n_window=args.n_window)
@@ -179,7 +185,8 @@ def main():
     for i in range(args.steps):
         ev[i][0].record()
         hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk)
+                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
+                                  top_r=args.top_r, workspace=ws)
         ev[i][1].record()
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
@@ -218,7 +225,7 @@ def main():
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
-                   "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk,
+                   "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "top_r": args.top_r,
                    "n_sink": args.n_sink, "n_window": args.n_window},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
         "mask_estimate": {"algorithmic_GB": mask_bytes / 1e9, "GB/s": mask_gbs, "frac_hbm_peak": mask_gbs / HBM_PEAK_GBS},
@@ -228,7 +235,8 @@ def main():
         "roofline": roof,
     }
     if args.cpu_budget > 0:
-        res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget)
+        res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget, n_sink=args.n_sink, n_window=args.n_window,
+                                           b_sq=args.b_sq, b_sk=args.b_sk, top_r=args.top_r)
     print(json.dumps(res))
 
 

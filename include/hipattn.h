@@ -47,7 +47,7 @@ enum {
     HIP_ATTN_OK = 0,
     HIP_ATTN_ENULL = -1,       /* a required pointer is NULL                                  */
     HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len,  */
-                               /* negative n_sink / n_window                                  */
+                               /* negative n_sink / n_window / top_r                          */
     HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1,   */
                                /* b_sq > bq, bk % b_sk != 0, unknown rep_pos                  */
     HIP_ATTN_EHEADDIM = -4,    /* head_dim not in {64, 128}                                   */
@@ -55,6 +55,7 @@ enum {
     HIP_ATTN_ETOOLARGE = -6,   /* k/bk above HIP_ATTN_MAX_KB, or bq*head_dim above the limit  */
     HIP_ATTN_EALIGN = -7,      /* a pointer or row stride is not 16-byte aligned              */
     HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0 */
+    HIP_ATTN_EWORKSPACE = -9,  /* workspace_bytes below hip_workspace_bytes()                 */
     HIP_ATTN_ELAUNCH = -1000   /* launch failure: code is HIP_ATTN_ELAUNCH - hipError_t       */
 };
 
@@ -102,6 +103,19 @@ typedef struct hip_problem {
     /* hip_mask_estimate only: which block of a branch represents it: HIP_ATTN_REP_CENTER (default,
      * paper Sec. 3.1), _FIRST or _LAST (the paper's appendix ablates the position). */
     int32_t rep_pos;
+    /* hip_mask_estimate only: top-r approximation of the scores (paper appendix "Top-r Approximation"):
+     * the products of a query row run over the top_r channels in which that row's |q| is largest (the
+     * lower channel among equal magnitudes); each row of a query block has its own channel set.
+     * 0 or >= head_dim = all channels (the default of the paper).  The call first writes a copy of Q
+     * with the other channels zeroed into `workspace` and estimates the mask from that copy: a row's
+     * channels are scattered over every 32-byte sector of a key row, so whole key rows are still
+     * fetched on this hardware and the option serves accuracy studies, not speed. */
+    int32_t top_r;
+    /* Device scratch owned by the caller, 16-byte aligned, at least hip_workspace_bytes(p) bytes; read and
+     * written by the call's kernels only, free for reuse once the stream has passed them.  May be NULL
+     * when hip_workspace_bytes(p) is 0 (every problem without top_r). */
+    void *workspace;
+    size_t workspace_bytes;
 } hip_problem;
 
 /*
@@ -132,8 +146,8 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
 int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const void *V,
                     const int32_t *indices, void *O, void *stream);
 
-/* Device scratch the two calls need for this problem (always 0 in this version: the
- * kernels keep their state in LDS and registers). */
+/* Device scratch hip_mask_estimate needs for this problem: one copy of Q when top_r is in use,
+ * otherwise 0 (the kernels keep their state in LDS and registers).  hip_sparse_attn needs none. */
 size_t hip_workspace_bytes(const hip_problem *p);
 
 /* Static, human-readable text for a return code. */

@@ -41,6 +41,7 @@ class _Problem(ctypes.Structure):
         ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
         ("n_threads", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
         ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32),
+        ("top_r", ctypes.c_int32),
     ]
 
 
@@ -88,6 +89,7 @@ class Problem:
     b_sq: int = 1        # mask estimation: score every b_sq-th row of the query block
     b_sk: int = 1        # mask estimation: score every b_sk-th key of the representative block
     rep_pos: int = 0     # mask estimation: representative block of a branch: 0 centre, 1 first, 2 last
+    top_r: int = 0       # mask estimation: channels of largest |q| used per query row (0 = all)
 
     @property
     def kb(self) -> int:
@@ -101,7 +103,7 @@ class Problem:
         keep = []
         p = _Problem(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.q_len,
                      self.max_kv_len, self.k, self.bq, self.bk, None, None, 0, 0, self.n_threads,
-                     self.n_sink, self.n_window, self.b_sq, self.b_sk, self.rep_pos)
+                     self.n_sink, self.n_window, self.b_sq, self.b_sk, self.rep_pos, self.top_r)
         if self.kv_lens is not None:
             a = np.ascontiguousarray(self.kv_lens, dtype=np.int32)
             assert a.shape == (self.batch,)

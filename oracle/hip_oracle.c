@@ -49,6 +49,7 @@ typedef struct {
      * position of a branch's representative block (Sec. 3.1 uses the centre; the appendix ablates others) */
     int32_t b_sq, b_sk;        /* <= 1: every query row / every key of the block */
     int32_t rep_pos;           /* 0 centre, 1 first block, 2 last block of the branch */
+    int32_t top_r;             /* 0 or >= head_dim: all channels; else channels kept per query row */
 } oracle_problem;
 
 /* Statistics of one mask-estimation unit, used by the structural pins. */
@@ -90,7 +91,7 @@ static int64_t rnd_div(int64_t a, int64_t b) { return (2 * a + b) / (2 * b); }
  *          then ORACLE_SENTINEL padding
  */
 static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K, int64_t kv_len,
-                      int kb, int bk, int b_sq, int b_sk, int rep_pos, int32_t *out, oracle_mask_stats *st)
+                      int kb, int bk, int b_sq, int b_sk, int rep_pos, int top_r, int32_t *out, oracle_mask_stats *st)
 {
     if (b_sq < 1) b_sq = 1;
     if (b_sk < 1) b_sk = 1;
@@ -108,6 +109,23 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
     int64_t *bs = malloc(sizeof(int64_t) * 2 * (size_t)kb), *be = malloc(sizeof(int64_t) * 2 * (size_t)kb);
     double *sc = malloc(sizeof(double) * 2 * (size_t)kb);
     char *keep = malloc(2 * (size_t)kb);
+
+    /* Top-r approximation (appendix "Top-r Approximation", its equation for q.k): a query row's dot
+     * products run over the r channels where |q| is largest only.  use[m*d + c] marks them; the
+     * channels are taken one by one, largest |q| first, the lower channel among equals. */
+    char *use = NULL;
+    if (top_r > 0 && top_r < d) {
+        use = calloc((size_t)n_rows * (size_t)d, 1);
+        for (int m = 0; m < n_rows; ++m) {
+            const float *qrow = q + (int64_t)m * d;
+            for (int l = 0; l < top_r; ++l) {
+                int arg = -1;
+                for (int c = 0; c < d; ++c)
+                    if (!use[(size_t)m * d + c] && (arg < 0 || fabs((double)qrow[c]) > fabs((double)qrow[arg]))) arg = c;
+                use[(size_t)m * d + arg] = 1;
+            }
+        }
+    }
 
     /* Initial nodes: kb equal chunks of the block range with rounded bounds
      * (Alg. 1 "set k nodes' initial start and end indices", block-wise per Sec. 3.2). */
@@ -147,7 +165,8 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
                     if (t > pos0 + m) continue;
                     const float *qrow = q + (int64_t)m * d;
                     double dot = 0.0;
-                    for (int c = 0; c < d; ++c) dot += (double)qrow[c] * (double)krow[c];
+                    for (int c = 0; c < d; ++c)
+                        if (!use || use[(size_t)m * d + c]) dot += (double)qrow[c] * (double)krow[c];
                     if (dot > best) best = dot;
                 }
             }
@@ -172,7 +191,7 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
     }
 
     for (int j = 0; j < n; ++j) out[j] = (int32_t)(ns[j] * bk);
-    free(ns); free(ne); free(bs); free(be); free(sc); free(keep);
+    free(ns); free(ne); free(bs); free(be); free(sc); free(keep); free(use);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -300,7 +319,7 @@ int oracle_hip_mask_estimate_units(const oracle_problem *p, const float *Q, cons
         int64_t pos0 = kv_len - p->q_len + row0;
         kv_view kv = make_view(p, K, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
-        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, out + u * kb,
+        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, p->top_r, out + u * kb,
                   stats ? stats + u : NULL);
     }
     return 0;

@@ -33,7 +33,8 @@ class HipProblem(ctypes.Structure):
         ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
         ("q_strides", ctypes.c_int64 * 3), ("kv_strides", ctypes.c_int64 * 3), ("o_strides", ctypes.c_int64 * 3),
         ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
-        ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32),
+        ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32), ("top_r", ctypes.c_int32),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
 
 
@@ -130,12 +131,18 @@ def poison_lds(pattern: int = 0xAAAAAAAA) -> None:
 
 def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,
                       flags: int = 0, indices: Optional[torch.Tensor] = None, b_sq: int = 1, b_sk: int = 1,
-                      rep_pos: int = 0) -> torch.Tensor:
+                      rep_pos: int = 0, top_r: int = 0, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """int32 indices [B, Hq, ceil(Tq/bq), k/bk] of the selected key blocks (see include/hipattn.h)."""
     _need_gpu(Q, K, kv_lens, page_table, indices)
     lib = load()
     p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
-    p.b_sq, p.b_sk, p.rep_pos = b_sq, b_sk, rep_pos
+    p.b_sq, p.b_sk, p.rep_pos, p.top_r = b_sq, b_sk, rep_pos, top_r
+    need = lib.hip_workspace_bytes(ctypes.byref(p))
+    if need:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+        assert workspace.is_cuda and workspace.is_contiguous() and workspace.numel() * workspace.element_size() >= need
+        p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     nqb = (p.q_len + bq - 1) // bq
     if indices is None:
         indices = torch.empty((p.batch, p.n_q_heads, nqb, k // bk), dtype=torch.int32, device=Q.device)

@@ -17,7 +17,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     if (p.batch < 0 || p.n_q_heads <= 0 || p.n_kv_heads <= 0 || p.q_len < 0 || p.max_kv_len < 0) return HIP_ATTN_ESHAPE;
     if (p.n_q_heads % p.n_kv_heads) return HIP_ATTN_ESHAPE;
     if (p.q_len > p.max_kv_len) return HIP_ATTN_ESHAPE;
-    if (p.n_sink < 0 || p.n_window < 0) return HIP_ATTN_ESHAPE;
+    if (p.n_sink < 0 || p.n_window < 0 || p.top_r < 0) return HIP_ATTN_ESHAPE;
     if (p.head_dim != 64 && p.head_dim != 128) return HIP_ATTN_EHEADDIM;
     if (p.dtype != HIP_ATTN_F32 && p.dtype != HIP_ATTN_BF16) return HIP_ATTN_EDTYPE;
     if (p.k <= 0 || p.bk <= 0 || p.bq <= 0 || p.k % p.bk) return HIP_ATTN_EBLOCK;
@@ -40,6 +40,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
     kp.b_sq = p.b_sq > 1 ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
+    kp.top_r = p.top_r >= p.head_dim ? 0 : p.top_r;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
         for (kp.page_shift = 0; (1 << kp.page_shift) < p.page_size;) ++kp.page_shift;
@@ -89,6 +90,18 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
+    if (kp.top_r > 0) {
+        // top-r scores: a copy of Q with the unused channels of every row zeroed goes to the workspace,
+        // and the kernels below read that copy (dense layout)
+        if (!p->workspace) return HIP_ATTN_ENULL;
+        if (!aligned16(p->workspace)) return HIP_ATTN_EALIGN;
+        if (p->workspace_bytes < hip_workspace_bytes(p)) return HIP_ATTN_EWORKSPACE;
+        hipError_t e = launch_topr_mask(kp, bf16, p->workspace, st);
+        if (e != hipSuccess) return launch_result(e);
+        kp.Q = p->workspace;
+        kp.qs_r = kp.d; kp.qs_h = (int64_t)kp.q_len * kp.d; kp.qs_b = kp.qs_h * kp.hq;
+        kp.top_r = 0;
+    }
     if (!generic && mask_mfma_supported(kp, bf16)) return launch_result(launch_mask_mfma(kp, st));
     if (!generic && mask_decode_supported(kp, bf16)) return launch_result(launch_mask_decode(kp, st));
     return launch_result(launch_mask_generic(kp, bf16, st));
@@ -112,7 +125,13 @@ int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const vo
     return launch_result(launch_attn_generic(kp, bf16, st));
 }
 
-size_t hip_workspace_bytes(const hip_problem *) { return 0; }
+size_t hip_workspace_bytes(const hip_problem *p)
+{
+    if (!p || p->top_r <= 0 || p->top_r >= p->head_dim) return 0;
+    if (p->batch <= 0 || p->n_q_heads <= 0 || p->q_len <= 0 || p->head_dim <= 0) return 0;
+    const size_t elem = p->dtype == HIP_ATTN_BF16 ? 2 : 4;
+    return (size_t)p->batch * (size_t)p->n_q_heads * (size_t)p->q_len * (size_t)p->head_dim * elem;
+}
 
 const char *hip_strerror(int code)
 {
@@ -126,6 +145,7 @@ const char *hip_strerror(int code)
         case HIP_ATTN_ETOOLARGE: return "k/bk or the number of work units exceeds the compiled maximum";
         case HIP_ATTN_EALIGN: return "pointer or stride not 16-byte aligned";
         case HIP_ATTN_EPAGE: return "invalid page table description";
+        case HIP_ATTN_EWORKSPACE: return "workspace smaller than hip_workspace_bytes()";
         default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
     }
 }
@@ -137,6 +157,6 @@ int hip_attn_poison_lds(uint32_t pattern, void *stream)
     return launch_result(hipGetLastError());
 }
 
-int hip_attn_version(void) { return 101; }
+int hip_attn_version(void) { return 102; }
 
 }  // extern "C"

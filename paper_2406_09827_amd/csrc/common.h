@@ -24,6 +24,7 @@ struct KParams {
     int32_t n_sink, n_window;  // sparse attention: always-attended first / most recent keys
     int32_t b_sq, b_sk;        // mask estimation: row / key sampling strides of the block score (>= 1)
     int32_t rep_pos;           // mask estimation: representative block of a branch: 0 centre, 1 first, 2 last
+    int32_t top_r;             // mask estimation: channels kept per query row, 0 = all
     float sm_scale;
 };
 

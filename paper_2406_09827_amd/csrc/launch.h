@@ -14,5 +14,6 @@ hipError_t launch_mask_decode(const KParams &p, hipStream_t st);
 bool attn_decode_supported(const KParams &p, bool bf16);
 hipError_t launch_attn_decode(const KParams &p, hipStream_t st);
 hipError_t launch_attn_generic(const KParams &p, bool bf16, hipStream_t st);
+hipError_t launch_topr_mask(const KParams &p, bool bf16, void *dst, hipStream_t st);
 
 }  // namespace hipattn

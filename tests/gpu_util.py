@@ -11,12 +11,12 @@ import paper_2406_09827_amd as hipattn
 from paper_2406_09827_amd import synth
 
 
-def oracle_problem(w, x, n_threads=8, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0):
+def oracle_problem(w, x, n_threads=8, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0, top_r=0):
     lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
     table = x["page_table"].cpu().numpy() if x["page_table"] is not None else None
     return oracle.Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
                           kv_lens=lens, page_table=table, page_size=w.page_size, n_threads=n_threads,
-                          n_sink=n_sink, n_window=n_window, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
+                          n_sink=n_sink, n_window=n_window, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r)
 
 
 def host(x):
@@ -28,11 +28,11 @@ def _max_len(w, x):
     return None if (x["page_table"] is not None and x["kv_lens"] is not None) else w.kv_len
 
 
-def gpu_mask(w, x, flags=0, b_sq=1, b_sk=1, rep_pos=0):
+def gpu_mask(w, x, flags=0, b_sq=1, b_sk=1, rep_pos=0, top_r=0):
     hipattn.poison_lds(0xAAAAAAAA)   # a kernel reading LDS it never wrote now sees a fixed, hostile value
     return hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                      page_table=x["page_table"], max_kv_len=_max_len(w, x), flags=flags,
-                                     b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
+                                     b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r)
 
 
 def gpu_attn(w, x, idx, flags=0, sm_scale=0.0, n_sink=0, n_window=0):
@@ -59,14 +59,15 @@ def agreement(a, b):
     return float((a == b).mean())
 
 
-def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0):
+def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0,
+             top_r=0):
     """Full comparison of one workload; returns (agreement, max output error)."""
     exact = w.integer if exact is None else exact
     x = synth.make_inputs(w, device="cuda", threads=4)
-    idx_gpu = gpu_mask(w, x, flags, b_sq, b_sk, rep_pos)
+    idx_gpu = gpu_mask(w, x, flags, b_sq, b_sk, rep_pos, top_r)
     out_gpu = gpu_attn(w, x, idx_gpu, flags, sm_scale, n_sink, n_window)
     torch.cuda.synchronize()
-    p = oracle_problem(w, x, n_sink=n_sink, n_window=n_window, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
+    p = oracle_problem(w, x, n_sink=n_sink, n_window=n_window, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r)
     hx = host(x)
     all_u = oracle.all_units(p)
     if units is None:

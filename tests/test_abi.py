@@ -67,6 +67,42 @@ def test_null_and_misaligned_pointers():
     assert lib.hip_workspace_bytes(ctypes.byref(p)) == 0
 
 
+def test_workspace_rules_of_top_r():
+    lib = hipattn.load()
+    p = _ok_problem()
+    fake = ctypes.c_void_p(4096)
+    p.top_r = 16
+    need = lib.hip_workspace_bytes(ctypes.byref(p))
+    assert need == p.batch * p.n_q_heads * p.q_len * p.head_dim * 2
+    assert lib.hip_mask_estimate(ctypes.byref(p), fake, fake, fake, None) == -1       # no workspace
+    p.workspace, p.workspace_bytes = 4096 + 4, need
+    assert lib.hip_mask_estimate(ctypes.byref(p), fake, fake, fake, None) == -7       # misaligned
+    p.workspace, p.workspace_bytes = 4096, need - 1
+    assert lib.hip_mask_estimate(ctypes.byref(p), fake, fake, fake, None) == -9       # too small
+    assert lib.hip_strerror(-9) not in (None, b"", b"unknown error")
+    p.top_r = -1
+    assert lib.hip_mask_estimate(ctypes.byref(p), fake, fake, fake, None) == -2
+    p.top_r = p.head_dim                                                              # all channels: no scratch
+    assert lib.hip_workspace_bytes(ctypes.byref(p)) == 0
+
+
+def test_ctypes_mirror_matches_the_header(tmp_path):
+    """Size and field offsets of the ctypes mirror against what a C compiler makes of include/hipattn.h."""
+    import subprocess
+    fields = [n for n, _ in hipattn.HipProblem._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hipattn.h"', 'int main(void) {',
+             '  printf("%zu\\n", sizeof(hip_problem));']
+    lines += [f'  printf("%zu\\n", offsetof(hip_problem, {n}));' for n in fields]
+    lines += ['  return 0; }']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(hipattn.HipProblem)
+    assert out[1:] == [getattr(hipattn.HipProblem, n).offset for n in fields]
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     q = torch.zeros(1, 1, 16, 64)

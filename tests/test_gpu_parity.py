@@ -205,6 +205,21 @@ def test_prefill_scoring_variants(flags, bq, bk, b_sq, b_sk, rep_pos):
         U.run_case(w, flags, units=units, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos)
 
 
+@pytest.mark.parametrize("top_r", [1, 16, 40, 127])
+def test_top_r_channels(top_r):
+    # scores over each query row's top_r strongest channels: prefill (bf16, d = 128), decode (ragged, paged) and fp32 d = 64
+    for integer in (True, False):
+        w = synth.Workload("variants_topr", 1, 4, 2, 128, 1500, 1500, 128, 32, 2, "bf16", rho=0.95, spike_every=512,
+                           integer=integer, seed=68)
+        nqb = w.n_query_blocks
+        U.run_case(w, 0, units=[(0, h, qb) for h in range(4) for qb in sorted({0, 3, 5, nqb // 2, nqb - 1})], top_r=top_r)
+        w = synth.Workload("variants_topr_dec", 4, 4, 2, 128, 1, 6000, 256, 1, 2, "bf16", rho=0.9, ragged=(300, 6000),
+                           page_size=16, integer=integer, seed=69)
+        U.run_case(w, 0, top_r=top_r)
+    U.run_case(synth.C1_INT, 0, top_r=min(top_r, 63))
+    U.run_case(synth.C1, 0, top_r=min(top_r, 63), b_sq=2, rep_pos=2)
+
+
 def test_fp32_scoring_variants():
     U.run_case(synth.C1_INT, 0, b_sq=4, b_sk=2, rep_pos=2)
     U.run_case(synth.C1, 0, b_sq=2, b_sk=1, rep_pos=1)

@@ -188,6 +188,48 @@ def test_p2_scoring_variants(integer):
     assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 1, 1, 8, 2, 1, 2, rep_pos=2), Q, K2)[0, 0, 0]) == [6]
 
 
+def _mask_channels(Q, r):
+    """Q with all but the r channels of largest |q| of every row set to zero (stable: the lower
+    channel wins a tie), written with numpy's sort rather than the oracle's pick-one-at-a-time loop."""
+    order = np.argsort(-np.abs(Q), axis=-1, kind="stable")[..., :r]
+    out = np.zeros_like(Q)
+    np.put_along_axis(out, order, np.take_along_axis(Q, order, axis=-1), axis=-1)
+    return out
+
+
+@pytest.mark.parametrize("integer", [True, False])
+def test_p2_top_r_channels(integer):
+    """Top-r approximation of the scores (appendix "Top-r Approximation"): identical to running the
+    literal transcription on queries whose other channels are zeroed; r = d (or 0) is the plain method;
+    and a case built so that r changes the selected block."""
+    rng = np.random.default_rng(41 if integer else 42)
+    d, n = 8, 0
+    for (bq, bk) in [(1, 1), (4, 2), (3, 4)]:
+        for r in (1, 3, 7):
+            for kb in (1, 3, 8):
+                for T in (7, 33, 64, 130):
+                    p = Problem(1, 2, 1, d, T, T, kb * bk, bq, bk, top_r=r)
+                    Q, K = _rand((1, 2, T, d), rng, integer), _rand((1, 1, T, d), rng, integer)
+                    idx = oracle.mask_estimate(p, Q, K)
+                    Qm = _mask_channels(Q, r)
+                    for qb in sorted({0, p.n_query_blocks // 2, p.n_query_blocks - 1}):
+                        for h in (0, 1):
+                            assert _valid(idx[0, h, qb]) == _literal_indices(p, Qm, K, 0, h, qb, T), (bq, bk, r, kb, T, qb)
+                            n += 1
+    assert n > 500
+    p0 = Problem(1, 2, 1, d, 130, 130, 16, 4, 2)
+    Q, K = _rand((1, 2, 130, d), rng, integer), _rand((1, 1, 130, d), rng, integer)
+    base = oracle.mask_estimate(p0, Q, K)
+    for r in (0, d, d + 5):
+        assert np.array_equal(base, oracle.mask_estimate(Problem(1, 2, 1, d, 130, 130, 16, 4, 2, top_r=r), Q, K))
+    # q = (1, 0.5): key A = (0, 10) has the larger full product (5 > 3), key B = (3, 0) the larger
+    # product over the single strongest channel of q (3 > 0)
+    Qh = np.array([1.0, 0.5], dtype=np.float32).reshape(1, 1, 1, 2)
+    Kh = np.array([[0, 10], [3, 0]], dtype=np.float32).reshape(1, 1, 2, 2)
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 2, 1, 2, 1, 1, 1), Qh, Kh)[0, 0, 0]) == [0]
+    assert _valid(oracle.mask_estimate(Problem(1, 1, 1, 2, 1, 2, 1, 1, 1, top_r=1), Qh, Kh)[0, 0, 0]) == [1]
+
+
 # ----------------------------------------------------------------------------- P3
 def test_p3_paper_visualisation_structure():
     T, k, bq, bk, d = 4096, 512, 32, 2, 8
