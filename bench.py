@@ -119,22 +119,73 @@ def cpu_baseline(w, x, budget_s: float, **variant):
                       f"{t:.1f} s wall, extrapolated linearly"}
 
 
+def _time_ms(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best = float("inf")
+    for _ in range(reps):
+        a.record()
+        fn()
+        b.record()
+        b.synchronize()
+        best = min(best, a.elapsed_time(b))
+    return best
+
+
+def measured_peaks():
+    """What this GPU sustains: a 1 GiB device copy (read + write) and back-to-back bf16 MFMAs."""
+    import torch
+    import paper_2406_09827_amd as hipattn
+    src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    ms_copy = _time_ms(lambda: hipattn.probe_copy(dst, src), 10)
+    red = torch.empty(hipattn.PROBE_READ_WORDS, dtype=torch.int32, device="cuda")
+    ms_read = _time_ms(lambda: hipattn.probe_read(red, src), 10)
+    wgs, iters = 256 * 8, 4096   # 8 workgroups per compute unit, four waves each
+    out = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    flops = hipattn.probe_mfma(out, wgs, iters)
+    ms_mfma = _time_ms(lambda: hipattn.probe_mfma(out, wgs, iters), 5)
+    return {"hbm_copy_GB/s": 2 * (1 << 30) / (ms_copy * 1e-3) / 1e9, "hbm_read_GB/s": (1 << 30) / (ms_read * 1e-3) / 1e9, "hbm_published_GB/s": HBM_PEAK_GBS,
+            "mfma_bf16_TFLOP/s": flops / (ms_mfma * 1e-3) / 1e12, "mfma_bf16_published_TFLOP/s": MFMA_BF16_PEAK_TFLOPS}
+
+
+def dense_yardstick(w, x):
+    """torch's dense causal attention on the same Q, K, V (external yardstick only)."""
+    import torch
+    import torch.nn.functional as F
+    g = w.n_q_heads // w.n_kv_heads
+    try:
+        fn = lambda: F.scaled_dot_product_attention(x["Q"], x["K"], x["V"], is_causal=True, enable_gqa=g > 1)
+        ms = _time_ms(fn, 3)
+    except Exception as e:  # the yardstick is optional: report why it is missing
+        return {"impl": "torch scaled_dot_product_attention", "error": f"{type(e).__name__}: {e}"[:200]}
+    flops = 4.0 * w.batch * w.n_q_heads * w.q_len * w.kv_len * w.head_dim / 2
+    return {"impl": "torch scaled_dot_product_attention (causal, dense)", "ms": ms, "TFLOP/s": flops / (ms * 1e-3) / 1e12}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "pd", "ps"])
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 disables")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--b-sq", type=int, default=1, help="query-row sampling stride of the block score (default: all rows)")
     ap.add_argument("--b-sk", type=int, default=1, help="key sampling stride of the block score (default: all keys)")
     ap.add_argument("--top-r", type=int, default=0,
-                    help="score over each query row's top-r channels only (default 0: all channels; generic kernel)")
+                    help="score over each query row's top-r channels only (default 0: all channels)")
     ap.add_argument("--n-sink", type=int, default=0, help="sink keys added in the sparse attention (default 0)")
     ap.add_argument("--n-window", type=int, default=0, help="sliding-window keys added in the sparse attention (default 0)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure what this GPU sustains on a 1 GiB device copy and on back-to-back bf16 MFMAs")
+    ap.add_argument("--dense-yardstick", action="store_true",
+                    help="also time torch's dense causal attention on the same tensors (prefill workloads up to "
+                         "128k tokens; external yardstick, not part of the path)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
@@ -195,8 +246,9 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    ms_mask = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    ms_attn = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    t_mask = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    t_attn = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    ms_mask, ms_attn = sum(t_mask) / args.steps, sum(t_attn) / args.steps
 
     mask_bytes = mask_algorithmic_bytes(w, kv_lens)
     attn_flops, attn_bytes = attn_algorithmic(w, kv_lens)
@@ -228,12 +280,18 @@ def main():
                    "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "top_r": args.top_r,
                    "n_sink": args.n_sink, "n_window": args.n_window},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
+        "kernel_ms_median": {"mask_estimate": t_mask[len(t_mask) // 2], "sparse_attn": t_attn[len(t_attn) // 2]},
+        "kernel_ms_min": {"mask_estimate": t_mask[0], "sparse_attn": t_attn[0]},
         "mask_estimate": {"algorithmic_GB": mask_bytes / 1e9, "GB/s": mask_gbs, "frac_hbm_peak": mask_gbs / HBM_PEAK_GBS},
         "sparse_attn": {"algorithmic_TFLOP": attn_flops / 1e12, "TFLOP/s": attn_tflops,
                         "frac_mfma_bf16_peak": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                         "gathered_GB": attn_bytes / 1e9, "GB/s": attn_gbs},
         "roofline": roof,
     }
+    if args.peaks:
+        res["measured_peaks"] = measured_peaks()
+    if args.dense_yardstick and w.q_len == w.kv_len and w.kv_len <= 131072 and not w.page_size:
+        res["dense_yardstick"] = dense_yardstick(w, x)
     if args.cpu_budget > 0:
         res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget, n_sink=args.n_sink, n_window=args.n_window,
                                            b_sq=args.b_sq, b_sk=args.b_sk, top_r=args.top_r)

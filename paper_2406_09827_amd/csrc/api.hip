@@ -157,6 +157,27 @@ int hip_attn_poison_lds(uint32_t pattern, void *stream)
     return launch_result(hipGetLastError());
 }
 
-int hip_attn_version(void) { return 102; }
+int hip_attn_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src) return HIP_ATTN_ENULL;
+    if (!aligned16(dst) || !aligned16(src) || bytes % 16) return HIP_ATTN_EALIGN;
+    return launch_result(launch_probe_copy(dst, src, (int64_t)bytes, static_cast<hipStream_t>(stream)));
+}
+
+int hip_attn_probe_read(uint32_t *out, const void *src, size_t bytes, void *stream)
+{
+    if (!out || !src) return HIP_ATTN_ENULL;
+    if (!aligned16(src) || bytes % 16) return HIP_ATTN_EALIGN;
+    return launch_result(launch_probe_read(out, src, (int64_t)bytes, static_cast<hipStream_t>(stream)));
+}
+
+int hip_attn_probe_mfma(float *out, int32_t workgroups, int32_t iters, void *stream)
+{
+    if (!out) return HIP_ATTN_ENULL;
+    if (workgroups <= 0 || iters <= 0) return HIP_ATTN_ESHAPE;
+    return launch_result(launch_probe_mfma(out, workgroups, iters, static_cast<hipStream_t>(stream)));
+}
+
+int hip_attn_version(void) { return 103; }
 
 }  // extern "C"

@@ -232,3 +232,21 @@ def test_decode_scoring_variants(flags, bk, b_sk, rep_pos, paged):
         w = synth.Workload("variants_dec", 6, 8, 2, 128, 1, 9000, 128 * bk, 1, bk, "bf16", rho=0.9, ragged=(300, 9000),
                            page_size=16 if paged else 0, integer=integer, seed=67)
         U.run_case(w, flags, b_sk=b_sk, rep_pos=rep_pos)
+
+
+def test_measurement_probes():
+    # the copy probe moves every byte; the MFMA probe runs and writes finite sums
+    import paper_2406_09827_amd as hipattn
+    src = torch.randint(0, 255, (3 * 1024 * 1024 + 16,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    hipattn.probe_copy(dst, src)
+    assert torch.equal(dst, src)
+    red = torch.zeros(hipattn.PROBE_READ_WORDS, dtype=torch.int32, device="cuda")
+    hipattn.probe_read(red, src)
+    words = src[:src.numel() // 4 * 4].view(torch.int32)
+    fold = lambda t: int(np.bitwise_xor.reduce(t.cpu().numpy().view(np.uint32)))
+    assert fold(red) == fold(words)
+    out = torch.full((8 * 256,), float("nan"), device="cuda")
+    assert hipattn.probe_mfma(out, 8, 16) == 8 * 4 * 16 * 4 * 2.0 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
