@@ -181,6 +181,8 @@ def main():
     ap.add_argument("--n-window", type=int, default=0, help="sliding-window keys added in the sparse attention (default 0)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
+    ap.add_argument("--seq-len", type=int, default=0,
+                    help="override the workload's context length (prefill: also its query length); scaling studies")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this GPU sustains on a 1 GiB device copy and on back-to-back bf16 MFMAs")
     ap.add_argument("--dense-yardstick", action="store_true",
@@ -198,6 +200,9 @@ def main():
 
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.seq_len > 0:
+        w = synth.scaled(w, kv_len=args.seq_len, q_len=args.seq_len if w.q_len == w.kv_len else w.q_len,
+                         name=f"{w.name}_T{args.seq_len}")
     flags = hipattn.FORCE_GENERIC if args.generic else 0
     t0 = time.perf_counter()
     x = synth.make_inputs(w, device="cuda", threads=16)
@@ -255,16 +260,17 @@ def main():
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
     attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
+    tag = args.workload if args.seq_len == 0 else "none"   # counter summaries exist for the named workloads only
     if ms_mask >= ms_attn:
         roof = {"kernel": "mask_estimate", "bound": "hbm", "achieved": mask_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{args.workload}")}
+                "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{tag}")}
     elif w.q_len == 1:  # vector x matrix: bandwidth bound
         roof = {"kernel": "sparse_attn", "bound": "hbm", "achieved": attn_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": attn_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"sparse_attn_{args.workload}")}
+                "frac": attn_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"sparse_attn_{tag}")}
     else:
         roof = {"kernel": "sparse_attn", "bound": "mfma", "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": read_traffic(f"sparse_attn_{args.workload}")}
+                "traffic": read_traffic(f"sparse_attn_{tag}")}
 
     if w.q_len < w.kv_len:  # decode: one (or, for speculative decoding, a few) new rows per sequence
         metric, unit, value, hib = f"HiP decode us/step @{w.kv_len // 1024}k ctx", "us/step", ms_step * 1e3, False
