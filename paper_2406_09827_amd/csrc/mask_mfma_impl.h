@@ -283,55 +283,47 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     };
 
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
-        // pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two
-        stage_t R0, R1;  // one vector value each, so the staged rows stay in registers
-        meta_t m0, m1;
-        int t0 = -1, s0 = ~0, t1 = -1, s1 = ~0;
-        read_meta(0, m0);
-        if (n_tiles > 1) read_meta(1, m1);
-        load_rows(0, m0, R0, t0, s0);
-        if (n_tiles > 2) read_meta(2, m0);
-        if (n_tiles > 1) {
-            load_rows(1, m1, R1, t1, s1);
-            if (n_tiles > 3) read_meta(3, m1);
-        }
-        // tile 0 goes into the LDS tile; from then on the tile after the one being multiplied is
-        // written to LDS (and the loads of the tile three ahead are issued) while the multiplies run
-        int tcur = t0, scur = s0;
-        park(R0);
-        if (2 < n_tiles) {
-            load_rows(2, m0, R0, t0, s0);
-            if (4 < n_tiles) read_meta(4, m0);
-        }
-        wave_lds_sync();
-        for (int tile = 0; tile < n_tiles; tile += 2) {
-            // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2
-            acc_t A;
-            score_issue(A);
-            int tn = -1, sn = -1;
-            if (tile + 1 < n_tiles) {
-                tn = t1; sn = s1;
-                park(R1);
-                if (tile + 3 < n_tiles) {
-                    load_rows(tile + 3, m1, R1, t1, s1);
-                    if (tile + 5 < n_tiles) read_meta(tile + 5, m1);
-                }
-            }
+        // Pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two.
+        // The loop body is straight-line code: tile numbers past the end are clamped to the last tile
+        // (it is then loaded and scored again, which rewrites the same keys), because a load that is
+        // issued on some paths only makes the compiler wait for ALL outstanding loads before it
+        // touches a staged register, and that exposes the full memory latency in every tile.
+        const int nt = __builtin_amdgcn_readfirstlane(n_tiles);
+        if (nt > 0) {
+            const int last_tile = nt - 1;
+            stage_t R0, R1;  // one vector value each, so the staged rows stay in registers
+            meta_t m0, m1;
+            int t0, s0, t1, s1;
+            read_meta(0, m0);
+            read_meta(min(1, last_tile), m1);
+            load_rows(0, m0, R0, t0, s0);
+            read_meta(min(2, last_tile), m0);
+            load_rows(min(1, last_tile), m1, R1, t1, s1);
+            read_meta(min(3, last_tile), m1);
+            // tile 0 goes into the LDS tile; from then on the tile after the one being multiplied is
+            // written to LDS (and the loads of the tile three ahead are issued) while the multiplies run
+            int tcur = t0, scur = s0;
+            park(R0);
+            load_rows(min(2, last_tile), m0, R0, t0, s0);
+            read_meta(min(4, last_tile), m0);
             wave_lds_sync();
-            score_finish(A, tcur, scur);
-            if (tile + 1 < n_tiles) {
+            for (int tile = 0; tile < nt; tile += 2) {
+                // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2
+                acc_t A;
+                score_issue(A);
+                const int tn = t1, sn = s1;
+                park(R1);
+                load_rows(min(tile + 3, last_tile), m1, R1, t1, s1);
+                read_meta(min(tile + 5, last_tile), m1);
+                wave_lds_sync();
+                score_finish(A, tcur, scur);
                 // tile+1 is in LDS, R0 holds tile+2, R1 tile+3
                 acc_t B;
                 score_issue(B);
-                tcur = -1; scur = -1;
-                if (tile + 2 < n_tiles) {
-                    tcur = t0; scur = s0;
-                    park(R0);
-                    if (tile + 4 < n_tiles) {
-                        load_rows(tile + 4, m0, R0, t0, s0);
-                        if (tile + 6 < n_tiles) read_meta(tile + 6, m0);
-                    }
-                }
+                tcur = t0; scur = s0;
+                park(R0);
+                load_rows(min(tile + 4, last_tile), m0, R0, t0, s0);
+                read_meta(min(tile + 6, last_tile), m0);
                 wave_lds_sync();
                 score_finish(B, tn, sn);
             }
