@@ -250,3 +250,49 @@ def test_measurement_probes():
     assert hipattn.probe_mfma(out, 8, 16) == 8 * 4 * 16 * 4 * 2.0 * 32 * 32 * 16
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
+
+
+# ---- seeded sweep over shapes and options (integer-valued inputs: indices must match bit for bit) ----
+
+def _sweep_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 4]))
+    bk = int(rng.choice([1, 2, 4, 8, 16]))
+    decode = bool(rng.integers(0, 2))
+    dtype = "bf16" if rng.integers(0, 4) else "fp32"
+    kb = int(rng.choice([1, 3, 8, 32, 64, 100, 256]))
+    paged = bool(rng.integers(0, 2))
+    page = int(rng.choice([bk, 2 * bk, 4 * bk, 16 * bk])) if paged else 0
+    if decode:
+        B, bq, q_len = int(rng.integers(1, 6)), 1, 1
+        T = int(rng.integers(1, 6000))
+        ragged = (max(1, T // 7), T) if rng.integers(0, 2) else None
+    else:
+        B = int(rng.integers(1, 3))
+        bq = int(rng.choice([1, 4, 16, 32, 48, 64]))
+        T = int(rng.integers(bq, 1800))
+        q_len = T if rng.integers(0, 3) else int(rng.integers(1, T + 1))   # sometimes a chunk of rows at the end
+        ragged = None
+    b_sk = int(rng.choice([x for x in (1, 2, 4) if bk % x == 0]))
+    b_sq = int(rng.choice([x for x in (1, 2, 4) if x <= bq]))
+    opts = dict(b_sq=b_sq, b_sk=b_sk, rep_pos=int(rng.integers(0, 3)),
+                n_sink=int(rng.choice([0, 0, 3, 16])), n_window=int(rng.choice([0, 0, 5, 64])),
+                top_r=int(rng.choice([0, 0, 0, 5, d // 2])))
+    w = synth.Workload(f"sweep{seed}", B, hkv * g, hkv, d, q_len, T, kb * bk, bq, bk, dtype, rho=0.9, ragged=ragged,
+                       page_size=page, integer=True, seed=4000 + seed)
+    return w, opts
+
+
+@pytest.mark.parametrize("seed", range(240))
+def test_seeded_shape_sweep(seed):
+    w, opts = _sweep_case(seed)
+    print(w, opts, flush=True)
+    units = None
+    if w.n_query_blocks * w.batch * w.n_q_heads > 400:
+        rng = np.random.default_rng(seed)
+        nqb = w.n_query_blocks
+        units = sorted({(int(rng.integers(0, w.batch)), int(rng.integers(0, w.n_q_heads)), int(q))
+                        for q in list(rng.integers(0, nqb, 60)) + [0, nqb - 1]})
+    U.run_case(w, 0, units=units, **opts)
