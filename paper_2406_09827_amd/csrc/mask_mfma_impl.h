@@ -180,77 +180,51 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         mt_.sl = final_mode ? fsl[min(ti, NB / 2 - 1)] : ti;  // (entries past the list are never used)
     };
 
-    // Coalesced loads of a tile's 32 rows from the metadata read earlier.
-    // t = key position of this lane's scored row, or -1 if the row does not count;
-    // slot = its branch slot, complemented when the branch is empty.
-    auto load_rows = [&](int tile, const meta_t &mt_, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
-        {
-            const int sl = mt_.sl, tf = mt_.m[SPL];
-            const int tt = tf + ((col & (BK - 1)) << ks);
-            t = (tf >= 0 && tt < kv_len) ? tt : -1;
-            // empty: in a normal round the slot is still named (complemented) so its key gets cleared;
-            // in the final round an entry past the end of the list names no slot at all
-            slot = tf >= 0 ? sl : (final_mode ? -1 : ~sl);
-        }
-        // per branch slot: offset of the block's first row; rows past the end of the sequence
-        // re-read its last row (their score is dropped: t < 0 above)
+    // Row info of a tile from the metadata read earlier: t = key position of this lane's scored row,
+    // or -1 if the row does not count; slot = its branch slot, complemented when the branch is empty.
+    auto row_info = [&](const meta_t &mt_, int &t, int &slot) __attribute__((always_inline)) {
+        const int sl = mt_.sl, tf = mt_.m[SPL];
+        const int tt = tf + ((col & (BK - 1)) << ks);
+        t = (tf >= 0 && tt < kv_len) ? tt : -1;
+        // empty: in a normal round the slot is still named (complemented) so its key gets cleared;
+        // in the final round an entry past the end of the list names no slot at all
+        slot = tf >= 0 ? sl : (final_mode ? -1 : ~sl);
+    };
+    // Coalesced load of row j (of NLD) of this lane's share of a tile.  Rows past the end of the
+    // sequence re-read its last row (their score is dropped: t < 0 in row_info).
+    auto load_row = [&](const meta_t &mt_, stage_t &R, int j) __attribute__((always_inline)) {
+        const int i = j / BK, n = j % BK;
+        const int tf = max(mt_.m[i], 0);
         const int last = kv_len - 1;
-#pragma unroll
-        for (int i = 0; i < SPL; ++i) {
-            const int tf = max(mt_.m[i], 0);
-            if (PAGED) {
-                // a block never straddles a page
-                const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
-#pragma unroll
-                for (int n = 0; n < BK; ++n) {
-                    const uint4 x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + (n << ks), last) - tf) * p.ks_r);
-                    const int j = i * BK + n;
-                    R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
-                }
-            } else {
-#pragma unroll
-                for (int n = 0; n < BK; ++n) {
-                    const uint4 x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + (n << ks), last) * row_bytes + (uint32_t)lc * 16u));
-                    const int j = i * BK + n;
-                    R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
-                }
-            }
+        uint4 x;
+        if (PAGED) {
+            // a block never straddles a page
+            const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
+            x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + (n << ks), last) - tf) * p.ks_r);
+        } else {
+            x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + (n << ks), last) * row_bytes + (uint32_t)lc * 16u));
         }
+        R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
+    };
+    auto load_rows = [&](const meta_t &mt_, stage_t &R, int &t, int &slot) __attribute__((always_inline)) {
+        row_info(mt_, t, slot);
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) load_row(mt_, R, j);
     };
 
     // registers -> swizzled LDS tile: row r = lg*NLD + j, chunk lc goes to slot lc ^ (r % CPR)
+    auto park_row = [&](const stage_t &R, int j) __attribute__((always_inline)) {
+        const int r = lg * NLD + j;
+        *(uint4 *)(tile_s + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) =
+            make_uint4(R[4 * j], R[4 * j + 1], R[4 * j + 2], R[4 * j + 3]);
+    };
     auto park = [&](const stage_t &R) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            const int r = lg * NLD + j;
-            *(uint4 *)(tile_s + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) =
-                make_uint4(R[4 * j], R[4 * j + 1], R[4 * j + 2], R[4 * j + 3]);
-        }
+        for (int j = 0; j < NLD; ++j) park_row(R, j);
     };
 
     struct acc_t { f32x16 a[MT]; };
-    // first half of scoring a tile: operand reads and the multiplies (they run on in the matrix pipe
-    // while the wave goes on with the next tile's LDS writes and loads)
-    auto score_issue = [&](acc_t &A) __attribute__((always_inline)) {
-        f32x16 (&acc)[MT] = A.a;
-#pragma unroll
-        for (int a = 0; a < MT; ++a)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
-        // all operand reads first (one LDS latency per tile, not one per k-step), then the multiplies
-        uint4 kv[KS];
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-            kv[kk] = *(const uint4 *)(tile_s + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
-        __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from re-interleaving reads and multiplies
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv[kk]), acc[mt], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // second half: branch score from the product tile, written as an ordered key
+    // Branch score from a tile of products, written as an ordered key
     auto score_finish = [&](const acc_t &A, int t, int slot) __attribute__((always_inline)) {
         const f32x16 (&acc)[MT] = A.a;
         // max over the admissible query rows of this lane's key column
@@ -282,6 +256,32 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         if (hh == 0 && (col & (BK - 1)) == 0 && (slot >= 0 || !final_mode)) keys[sl] = slot < 0 ? 0u : score_key(v);
     };
 
+    static_assert(NLD == KS, "one staged row per k-step");
+    // One pipeline step: multiplies the tile that sits in LDS (operands are read into registers first)
+    // and, between the multiplies, moves the staged tile R into the LDS tile row by row and refills R
+    // with the rows of the tile named by mt_.  The order is pinned: left to itself the compiler issues
+    // the multiplies back to back, and the wave then waits on the matrix pipe with all of this
+    // independent work behind it.
+    auto multiply_and_restage = [&](acc_t &A, stage_t &R, const meta_t &mt_, int &t, int &slot) __attribute__((always_inline)) {
+        f32x16 (&acc)[MT] = A.a;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // all operand reads first (one LDS latency per tile, not one per k-step)
+        uint4 kv[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+            kv[kk] = *(const uint4 *)(tile_s + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
+        row_info(mt_, t, slot);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[mt][kk], __builtin_bit_cast(bf16x8, kv[kk]), kk == 0 ? zero : acc[mt], 0, 0, 0);
+            park_row(R, kk);
+            load_row(mt_, R, kk);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         // Pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two.
         // The loop body is straight-line code: tile numbers past the end are clamped to the last tile
@@ -296,33 +296,30 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             int t0, s0, t1, s1;
             read_meta(0, m0);
             read_meta(min(1, last_tile), m1);
-            load_rows(0, m0, R0, t0, s0);
+            load_rows(m0, R0, t0, s0);
             read_meta(min(2, last_tile), m0);
-            load_rows(min(1, last_tile), m1, R1, t1, s1);
+            load_rows(m1, R1, t1, s1);
             read_meta(min(3, last_tile), m1);
             // tile 0 goes into the LDS tile; from then on the tile after the one being multiplied is
-            // written to LDS (and the loads of the tile three ahead are issued) while the multiplies run
+            // written to LDS (and the loads of the tile three ahead are issued) between the multiplies
             int tcur = t0, scur = s0;
             park(R0);
-            load_rows(min(2, last_tile), m0, R0, t0, s0);
+            load_rows(m0, R0, t0, s0);
             read_meta(min(4, last_tile), m0);
             wave_lds_sync();
             for (int tile = 0; tile < nt; tile += 2) {
-                // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2
+                // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2,
+                // m1 the branch-table entries of tile+3, m0 those of tile+4
                 acc_t A;
-                score_issue(A);
                 const int tn = t1, sn = s1;
-                park(R1);
-                load_rows(min(tile + 3, last_tile), m1, R1, t1, s1);
+                multiply_and_restage(A, R1, m1, t1, s1);
                 read_meta(min(tile + 5, last_tile), m1);
                 wave_lds_sync();
                 score_finish(A, tcur, scur);
                 // tile+1 is in LDS, R0 holds tile+2, R1 tile+3
                 acc_t B;
-                score_issue(B);
                 tcur = t0; scur = s0;
-                park(R0);
-                load_rows(min(tile + 4, last_tile), m0, R0, t0, s0);
+                multiply_and_restage(B, R0, m0, t0, s0);
                 read_meta(min(tile + 6, last_tile), m0);
                 wave_lds_sync();
                 score_finish(B, tn, sn);
