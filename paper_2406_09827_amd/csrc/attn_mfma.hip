@@ -126,13 +126,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     // value rows coalesced.  Rows that do not count load row 0 of the sequence (always mapped,
     // finite) and get probability 0.  Returns flags: bit 0 = some key may count for some row,
     // bit 1 = some (key, row) pair needs masking, bit 2 = window tile.
-    auto fetch = [&](int tile, stage_t &RK, stage_t &RV, int *tk) __attribute__((always_inline)) {
+    // The index entry lane `col` needs for a tile of selected blocks is loaded one tile before fetch()
+    // uses it, so that the row loads do not queue behind the latency of the index load.
+    auto index_entry = [&](int tile) __attribute__((always_inline)) {
+        const int ki = tile * 32 + col;
+        return (tile < tiles_sel && ki < n_keys) ? idx[ki >> log_bk] : -1;
+    };
+    auto fetch = [&](int tile, int first, stage_t &RK, stage_t &RV, int *tk) __attribute__((always_inline)) {
         int t_c = -1;
         int flags;
         if (tile < tiles_sel) {
             const int ki = tile * 32 + col;
             if (ki < n_keys) {
-                const int first = idx[ki >> log_bk];
                 const int t = first + (ki & (bk - 1));
                 if (first >= 0 && first < kv_len && t < kv_len && t >= p.n_sink) t_c = t;
             }
@@ -191,7 +196,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     };
 
     stage_t RK, RV;
-    int flags_next = fetch(0, RK, RV, tk_s[wave][0]);
+    int flags_next = fetch(0, index_entry(0), RK, RV, tk_s[wave][0]);
+    int first_next = index_entry(1);
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int flags = flags_next;
         const int *tk = tk_s[wave][tile & 1];
@@ -202,7 +208,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             *(uint4 *)(kt + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) = make_uint4(RK[4 * j], RK[4 * j + 1], RK[4 * j + 2], RK[4 * j + 3]);
             *(uint4 *)(vt + r * PITCH + lc * 8) = make_uint4(RV[4 * j], RV[4 * j + 1], RV[4 * j + 2], RV[4 * j + 3]);
         }
-        if (tile + 1 < n_tiles) flags_next = fetch(tile + 1, RK, RV, tk_s[wave][(tile + 1) & 1]);
+        if (tile + 1 < n_tiles) {
+            flags_next = fetch(tile + 1, first_next, RK, RV, tk_s[wave][(tile + 1) & 1]);
+            first_next = index_entry(tile + 2);
+        }
         wave_lds_sync();
 
         if (flags & 1) {
