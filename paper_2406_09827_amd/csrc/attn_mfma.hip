@@ -114,6 +114,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     uint32_t *mo = mo_s[wave];
 
     const float c = p.sm_scale * 1.44269504088896340736f;  // scores are kept in log2 units
+    constexpr float kSlack = 8.f;
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 oacc[CT];
 #pragma unroll
@@ -250,8 +251,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             // raw scores here; the scale (c > 0) is applied to the maximum and inside the exponent
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
-            const float m_new = fmaxf(m_run, mx);
+            {   // other half of the query's keys: lane ^ 32
+                const unsigned u = __float_as_uint(mx);
+                auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * c;
+            }
+            // The running reference m_run only has to bound the exponents, it need not be the exact
+            // maximum: it moves (and the accumulators are rescaled) only when a tile's maximum exceeds
+            // it by more than kSlack (log2 units; probabilities then stay below 2^kSlack, far inside
+            // the range of fp32 sums and bf16 operands).  The final division by l cancels the reference.
+            const float m_new = mx > m_run + kSlack ? mx : m_run;
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
             float lsum = 0.f;
