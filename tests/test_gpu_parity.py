@@ -279,7 +279,7 @@ def _sweep_case(seed):
     b_sq = int(rng.choice([x for x in (1, 2, 4) if x <= bq]))
     opts = dict(b_sq=b_sq, b_sk=b_sk, rep_pos=int(rng.integers(0, 3)),
                 n_sink=int(rng.choice([0, 0, 3, 16])), n_window=int(rng.choice([0, 0, 5, 64])),
-                top_r=int(rng.choice([0, 0, 0, 5, d // 2])))
+                top_r=int(rng.choice([0, 0, 0, 5, d // 2])), sm_scale=float(rng.choice([0.0, 0.0, 0.03, 0.4, 1.5])))
     w = synth.Workload(f"sweep{seed}", B, hkv * g, hkv, d, q_len, T, kb * bk, bq, bk, dtype, rho=0.9, ragged=ragged,
                        page_size=page, integer=True, seed=4000 + seed)
     return w, opts
@@ -296,3 +296,14 @@ def test_seeded_shape_sweep(seed):
         units = sorted({(int(rng.integers(0, w.batch)), int(rng.integers(0, w.n_q_heads)), int(q))
                         for q in list(rng.integers(0, nqb, 60)) + [0, nqb - 1]})
     U.run_case(w, 0, units=units, **opts)
+
+
+@pytest.mark.parametrize("sm_scale", [0.5, 0.01])
+def test_softmax_scale_extremes(sm_scale):
+    # a scale that makes the softmax nearly one-hot (running maximum jumps by far more than the lazy-rescale
+    # slack) and one that makes it nearly uniform; prefill and decode
+    w = synth.scaled(synth.C2, q_len=3000, kv_len=3000, n_q_heads=4, n_kv_heads=2, spike_every=700)
+    nqb = w.n_query_blocks
+    U.run_case(w, 0, units=[(0, h, qb) for h in range(4) for qb in (0, 5, 20, nqb // 2, nqb - 1)], sm_scale=sm_scale)
+    U.run_case(synth.scaled(synth.C3, batch=3, kv_len=9000), 0, sm_scale=sm_scale)
+    U.run_case(synth.scaled(synth.C5, batch=5, kv_len=7000, ragged=(400, 7000)), 0, sm_scale=sm_scale, n_sink=4, n_window=32)
