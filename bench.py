@@ -183,6 +183,9 @@ def main():
                     help="also run one 1 GiB device copy (counter calibration for rocprofv3 --pmc runs)")
     ap.add_argument("--seq-len", type=int, default=0,
                     help="override the workload's context length (prefill: also its query length); scaling studies")
+    ap.add_argument("--refresh-period", type=int, default=1,
+                    help="decode only: estimate the mask every R-th step and reuse it in between (Alg. 2's mask "
+                         "refresh period); combine with --n-window >= R so that the newest keys stay attended")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this GPU sustains on a 1 GiB device copy and on back-to-back bf16 MFMAs")
     ap.add_argument("--dense-yardstick", action="store_true",
@@ -216,10 +219,13 @@ def main():
     # scratch of the top-r pre-pass (a copy of Q), allocated once outside the timed region
     ws = torch.empty(x["Q"].numel() * x["Q"].element_size(), dtype=torch.uint8, device="cuda") if args.top_r else None
 
-    def step():
-        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                  top_r=args.top_r, workspace=ws)
+    refresh = max(1, args.refresh_period) if w.q_len < w.kv_len else 1
+
+    def step(i=0):
+        if i % refresh == 0:
+            hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                      max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
+                                      top_r=args.top_r, workspace=ws)
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
                                 n_sink=args.n_sink, n_window=args.n_window)
@@ -231,8 +237,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     # events are recorded on torch's current stream, the stream the kernels are launched on
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -240,9 +246,10 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                  top_r=args.top_r, workspace=ws)
+        if i % refresh == 0:
+            hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                      max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
+                                      top_r=args.top_r, workspace=ws)
         ev[i][1].record()
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
@@ -251,9 +258,9 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    t_mask = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    t_mask = sorted(e[0].elapsed_time(e[1]) for i, e in enumerate(ev) if i % refresh == 0)   # per launch
     t_attn = sorted(e[1].elapsed_time(e[2]) for e in ev)
-    ms_mask, ms_attn = sum(t_mask) / args.steps, sum(t_attn) / args.steps
+    ms_mask, ms_attn = sum(t_mask) / len(t_mask), sum(t_attn) / len(t_attn)
 
     mask_bytes = mask_algorithmic_bytes(w, kv_lens)
     attn_flops, attn_bytes = attn_algorithmic(w, kv_lens)
@@ -284,7 +291,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
                    "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "top_r": args.top_r,
-                   "n_sink": args.n_sink, "n_window": args.n_window},
+                   "n_sink": args.n_sink, "n_window": args.n_window, "refresh_period": refresh},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
         "kernel_ms_median": {"mask_estimate": t_mask[len(t_mask) // 2], "sparse_attn": t_attn[len(t_attn) // 2]},
         "kernel_ms_min": {"mask_estimate": t_mask[0], "sparse_attn": t_attn[0]},
