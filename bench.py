@@ -29,10 +29,12 @@ def rounds_of(Tb: int, kb: int) -> int:
     return (c - 1).bit_length()
 
 
-def mask_algorithmic_bytes(w, kv_lens) -> float:
+def mask_algorithmic_bytes(w, kv_lens, rep_pos: int = 0) -> float:
     """Key bytes the method has to touch in mask estimation, counted conservatively:
     every round but a unit's last scores 2*kb branches, the last at least kb (nodes that are
-    already one block long have a single branch); plus the query block once and the indices."""
+    already one block long have a single branch); plus the query block once and the indices.
+    With the first or last block as representative, a child that shares its parent's representative
+    needs no new bytes: one round of 2*kb branches, kb per later round."""
     size = 2 if w.dtype == "bf16" else 4
     row = w.head_dim * size
     total = 0.0
@@ -44,7 +46,10 @@ def mask_algorithmic_bytes(w, kv_lens) -> float:
             L = min(kv_len, kv_len - w.q_len + r0 + n)
             Tb = -(-L // w.bk) if L > 0 else 0
             R = rounds_of(Tb, w.kb)
-            branches = (R - 1) * 2 * w.kb + w.kb if R > 0 else 0
+            if rep_pos == 0:
+                branches = (R - 1) * 2 * w.kb + w.kb if R > 0 else 0
+            else:
+                branches = (R + 1) * w.kb if R > 0 else 0
             total += branches * w.bk * row + n * row + w.kb * 4
     return total * w.n_q_heads
 
@@ -175,6 +180,8 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--b-sq", type=int, default=1, help="query-row sampling stride of the block score (default: all rows)")
     ap.add_argument("--b-sk", type=int, default=1, help="key sampling stride of the block score (default: all keys)")
+    ap.add_argument("--rep-pos", type=int, default=0, choices=[0, 1, 2],
+                    help="representative block of a branch: 0 centre (default), 1 first, 2 last")
     ap.add_argument("--top-r", type=int, default=0,
                     help="score over each query row's top-r channels only (default 0: all channels)")
     ap.add_argument("--n-sink", type=int, default=0, help="sink keys added in the sparse attention (default 0)")
@@ -225,7 +232,7 @@ def main():
         if i % refresh == 0:
             hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
                                       max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                      top_r=args.top_r, workspace=ws)
+                                      rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws)
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
                                 n_sink=args.n_sink, n_window=args.n_window)
@@ -249,7 +256,7 @@ def main():
         if i % refresh == 0:
             hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
                                       max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                      top_r=args.top_r, workspace=ws)
+                                      rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws)
         ev[i][1].record()
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
@@ -262,7 +269,7 @@ def main():
     t_attn = sorted(e[1].elapsed_time(e[2]) for e in ev)
     ms_mask, ms_attn = sum(t_mask) / len(t_mask), sum(t_attn) / len(t_attn)
 
-    mask_bytes = mask_algorithmic_bytes(w, kv_lens)
+    mask_bytes = mask_algorithmic_bytes(w, kv_lens, args.rep_pos)
     attn_flops, attn_bytes = attn_algorithmic(w, kv_lens)
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
@@ -290,7 +297,7 @@ def main():
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
-                   "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "top_r": args.top_r,
+                   "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "rep_pos": args.rep_pos, "top_r": args.top_r,
                    "n_sink": args.n_sink, "n_window": args.n_window, "refresh_period": refresh},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
         "kernel_ms_median": {"mask_estimate": t_mask[len(t_mask) // 2], "sparse_attn": t_attn[len(t_attn) // 2]},
@@ -307,7 +314,7 @@ def main():
         res["dense_yardstick"] = dense_yardstick(w, x)
     if args.cpu_budget > 0:
         res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget, n_sink=args.n_sink, n_window=args.n_window,
-                                           b_sq=args.b_sq, b_sk=args.b_sk, top_r=args.top_r)
+                                           b_sq=args.b_sq, b_sk=args.b_sk, rep_pos=args.rep_pos, top_r=args.top_r)
     print(json.dumps(res))
 
 

@@ -1,217 +1,9 @@
-// Hierarchical mask estimation for single-query decode in bf16 (paper Alg. 2: one run of
-// Alg. 1 per step over the current context, with bq = 1).
-//
-// With one query row the branch scoring is vector x gathered-rows work: bandwidth bound, no
-// use for the matrix cores.  One WAVE per (sequence, query head); the four waves of a
-// workgroup are the query heads of one KV group when Hq/Hkv = 4, so in the first round,
-// where all heads of a group score the same representative blocks, their loads meet in the
-// L1/L2 instead of going to HBM four times.
-//   * a key row is read by D/8 lanes, 16 bytes each (a full 128-bit coalesced row segment),
-//     multiplied with v_dot2_f32_bf16 and summed over the lanes with DPP adds;
-//   * two stages of 16 (8 at large batch) row loads per lane alternate, so up to 32 KB per wave are in flight
-//     (a wave is alone on its SIMD at small batch, the memory pipeline has to be kept full
-//     from inside the wave);
-//   * scores -> per-wave LDS keys -> ordered threshold selection (once per wave, nothing
-//     redundant) -> the wave's private node list.  No workgroup barrier anywhere.
-// Ragged lengths (kv_lens) and a page table are handled per row.
-#include "common.h"
-#include "launch.h"
+// Decode mask estimation: the default variant (centre representative) and the dispatch.
+#include "mask_decode_impl.h"
 
 namespace hipattn {
 
-// SPLIT = false: one wave per (sequence, head), four independent problems per workgroup.
-// SPLIT = true : one workgroup per (sequence, head); the four waves score a quarter of the
-//                branches each (stage i goes to wave i % 4), meet at a barrier, run the selection
-//                redundantly and write a quarter of the survivors each.  Used at small batch,
-//                where one wave per SIMD cannot keep enough loads in flight.
-template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xcd_map)
-{
-    constexpr int NB = 64 * E;
-    constexpr int LPR = D / 8;        // lanes per key row
-    constexpr int RPW = 64 / LPR;     // rows (= branches) per wave-wide load
-    constexpr int U = ROWS / BK;      // branches per lane group and stage: ROWS row loads per lane, two stages in flight
-    typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
-    constexpr int NW = SPLIT ? 1 : 4;  // private copies of the per-problem LDS state
-    constexpr int WS = SPLIT ? 4 : 1;  // waves sharing one problem
-    __shared__ uint32_t keys_s[NW][NB];
-    __shared__ int nds[NW][2][NB / 2], nde[NW][2][NB / 2];
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = lane / LPR, lc = lane % LPR;
-    const int own = SPLIT ? 0 : wave;  // which LDS copy
-    int64_t wg;
-    if (SPLIT) {
-        // keep the query heads of a KV group on one XCD (blockIdx.x % 8), next to each other in time
-        const int64_t bid = blockIdx.x;
-        if (xcd_map) {
-            const int64_t seq = bid >> 3, gi = (bid & 7) + 8 * (seq / p.g);
-            wg = gi * p.g + seq % p.g;  // = (b * hkv + hk) * g + head in group = b * hq + h
-        } else {
-            wg = bid;
-        }
-    } else {
-        wg = (int64_t)blockIdx.x * 4 + wave;
-    }
-    if (wg >= (int64_t)p.batch * p.hq) return;
-    const int b = (int)(wg / p.hq), h = (int)(wg % p.hq), hk = h / p.g;
-    const int kb = p.kb;
-    const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
-    int32_t *out = p.idx_out + wg * kb;
-
-    // BK = key rows scored per block; with a key sampling stride the block itself is bk = BK * b_sk keys
-    const int bsk = p.b_sk, bk = BK * bsk;
-    const int Tb = kv_len > 0 ? (kv_len + bk - 1) / bk : 0;
-    if (Tb <= kb) {
-        for (int j = SPLIT ? (int)threadIdx.x : lane; j < kb; j += SPLIT ? kThreads : 64) out[j] = j < Tb ? j * bk : kSentinel;
-        return;
-    }
-    // all waves of a problem hold identical copies of its state when SPLIT
-    auto sync_problem = [&]() __attribute__((always_inline)) {
-        if (SPLIT) __syncthreads(); else wave_lds_sync();
-    };
-    const int tix = SPLIT ? (int)threadIdx.x : lane, tn = SPLIT ? kThreads : 64;
-
-    const uint4 qv = *(const uint4 *)((const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + lc * 8);
-    uint32_t *keys = keys_s[own];
-    for (int i = tix; i < NB; i += tn) keys[i] = 0;
-    {
-        const int a = Tb / kb, r = Tb % kb;
-        for (int j = tix; j < kb; j += tn) {
-            nds[own][0][j] = chunk_bound(j, a, r, kb);
-            nde[own][0][j] = chunk_bound(j + 1, a, r, kb);
-        }
-    }
-    sync_problem();
-
-    const bf16_t *Kbase = (const bf16_t *)p.K;
-    int cur = 0;
-    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
-        const int *ns = nds[own][cur], *ne = nde[own][cur];
-
-        // one stage = U branches per lane group: node lookup, then the (unconditional) loads of
-        // the representative block's BK rows.  t0 < 0 marks an empty branch.
-        auto fetch = [&](int base, stage_t &kv, int (&t0)[U]) __attribute__((always_inline)) {
-            int pg[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int slot = base + u * RPW + grp, node = slot >> 1;
-                bool ok = node < kb;
-                int t = 0;
-                if (ok) {
-                    const int s = ns[node], e = ne[node];
-                    const int mid = s + ((e - s) >> 1);
-                    const int bs = (slot & 1) ? mid : s, be = (slot & 1) ? e : mid;
-                    ok = be > bs;
-                    if (ok) t = rep_block(bs, be, p.rep_pos) * bk;
-                }
-                t0[u] = ok ? t : -1;
-                pg[u] = page_of_row<PAGED>(p, b, ok ? t : 0);  // all page lookups of the stage first
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = t0[u] >= 0 ? t0[u] : 0;
-                const bf16_t *src = Kbase + row_offset_in<PAGED>(p, b, hk, t, pg[u]) + lc * 8;
-#pragma unroll
-                for (int n = 0; n < BK; ++n) {
-                    // rows past the end of the sequence re-read its last row and are ignored below
-                    const int dn = t0[u] >= 0 ? min(n * bsk, kv_len - 1 - t) : 0;
-                    const uint4 x = *(const uint4 *)(src + (int64_t)dn * p.ks_r);
-                    const int q4 = 4 * (u * BK + n);
-                    kv[q4] = x.x; kv[q4 + 1] = x.y; kv[q4 + 2] = x.z; kv[q4 + 3] = x.w;
-                }
-            }
-        };
-        auto score = [&](int base, const stage_t &kv, const int (&t0)[U]) __attribute__((always_inline)) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float best = -INFINITY;
-#pragma unroll
-                for (int n = 0; n < BK; ++n) {
-                    const int q4 = 4 * (u * BK + n);
-                    const float dsum = row_group_sum<LPR>(dot8_bf16(qv, make_uint4(kv[q4], kv[q4 + 1], kv[q4 + 2], kv[q4 + 3])));
-                    if (t0[u] + n * bsk < kv_len) best = fmaxf(best, dsum);
-                }
-                const int slot = base + u * RPW + grp;
-                if (lc == 0 && slot < NB) keys[slot] = t0[u] >= 0 ? score_key(best) : 0u;
-            }
-        };
-
-        constexpr int STEP = RPW * U;   // branches per stage
-        constexpr int STRIDE = WS * STEP;  // distance between two stages of the same wave
-        stage_t ka, kbuf;
-        int ta[U], tb[U];
-        const int first = SPLIT ? wave * STEP : 0;
-        if (first < 2 * kb) fetch(first, ka, ta);
-        for (int base = first; base < 2 * kb; base += 2 * STRIDE) {
-            const bool has_b = base + STRIDE < 2 * kb;
-            if (has_b) fetch(base + STRIDE, kbuf, tb);
-            score(base, ka, ta);
-            if (has_b) {
-                if (base + 2 * STRIDE < 2 * kb) fetch(base + 2 * STRIDE, ka, ta);
-                score(base + STRIDE, kbuf, tb);
-            }
-        }
-        sync_problem();
-
-        uint32_t key[E];
-        bool keep[E];
-        int dest[E];
-#pragma unroll
-        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
-        select_topk_ordered<E>(key, kb, keep, dest);
-        int *ns2 = nds[own][cur ^ 1], *ne2 = nde[own][cur ^ 1];
-#pragma unroll
-        for (int i = 0; i < E; ++i) {
-            if (keep[i] && (!SPLIT || (i & 3) == wave)) {
-                const int slot = i * 64 + lane, node = slot >> 1;
-                const int s = ns[node], e = ne[node];
-                const int mid = s + ((e - s) >> 1);
-                ns2[dest[i]] = (slot & 1) ? mid : s;
-                ne2[dest[i]] = (slot & 1) ? e : mid;
-            }
-        }
-        cur ^= 1;
-        sync_problem();
-    }
-
-    const int *ns = nds[own][cur];
-    for (int j = tix; j < kb; j += tn) out[j] = ns[j] * bk;
-}
-
-template <int BK, int D, int ROWS, bool SPLIT>
-static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t st)
-{
-    dim3 block(kThreads);
-#define HIPATTN_LAUNCH(EV)                                                                                  \
-    do {                                                                                                    \
-        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true, SPLIT>), grid, block, 0, st, p, xcd_map);  \
-        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false, SPLIT>), grid, block, 0, st, p, xcd_map);       \
-    } while (0)
-    if (p.kb <= 128) HIPATTN_LAUNCH(4);
-    else if (p.kb <= 256) HIPATTN_LAUNCH(8);
-    else HIPATTN_LAUNCH(16);
-#undef HIPATTN_LAUNCH
-    return hipGetLastError();
-}
-
-// Few problems (small batch): a workgroup per (sequence, head), four waves sharing the scoring, so
-// that enough loads are in flight per compute unit.  Many problems: a wave per problem; shallower
-// stages need fewer registers, so more waves fit a SIMD and hide each other's latency (including the
-// page-table lookups).
-template <int BK, int D>
-static hipError_t launch_e(const KParams &p, hipStream_t st)
-{
-    const int64_t problems = (int64_t)p.batch * p.hq;
-    if (problems < 2048) {
-        const int64_t groups = (int64_t)p.batch * p.hkv;
-        const int xcd_map = groups % 8 == 0 ? 1 : 0;
-        return launch_r<BK, D, 8, true>(p, dim3((unsigned)problems), xcd_map, st);
-    }
-    dim3 grid((unsigned)((problems + 3) / 4));
-    if (problems >= 4096) return launch_r<BK, D, 8, false>(p, grid, 0, st);
-    return launch_r<BK, D, 16, false>(p, grid, 0, st);
-}
+hipError_t launch_mask_decode_carry(const KParams &p, hipStream_t st);  // mask_decode_carry.hip
 
 bool mask_decode_supported(const KParams &p, bool bf16)
 {
@@ -221,16 +13,7 @@ bool mask_decode_supported(const KParams &p, bool bf16)
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
 {
-    if ((int64_t)p.batch * p.hq == 0) return hipSuccess;
-    const int rows = p.bk / p.b_sk;
-    if (p.d == 64) {
-        if (rows == 1) return launch_e<1, 64>(p, st);
-        if (rows == 2) return launch_e<2, 64>(p, st);
-        return launch_e<4, 64>(p, st);
-    }
-    if (rows == 1) return launch_e<1, 128>(p, st);
-    if (rows == 2) return launch_e<2, 128>(p, st);
-    return launch_e<4, 128>(p, st);
+    return p.rep_pos != 0 ? launch_mask_decode_carry(p, st) : launch_mask_decode_variant<false>(p, st);
 }
 
 }  // namespace hipattn

@@ -149,11 +149,13 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
-    // Final round with the centre representative: every node is one or two blocks long.  A
-    // one-block node IS its representative and the right half of a two-block node is the
-    // node's representative, so their scores are carried over from the round that kept the
-    // node; only the left halves of two-block nodes are scored.  In that round the branch table
-    // is a compact list of those blocks and fsl[] names the slot each one belongs to.
+    // Rounds that run from a compact list.  A child that has its parent's representative block has the
+    // parent's score, which is carried over from the round that kept the parent, and only the other
+    // child is gathered and scored: with the first (last) block as representative that is the left
+    // (right) child in every round after the first; with the centre representative it happens in the
+    // final round, where every node is one or two blocks long, a one-block node IS its representative
+    // and the right half of a two-block node is the node's representative.  In such a round the branch
+    // table is a compact list of the blocks to score and fsl[] names the slot each one belongs to.
     bool final_mode = false;
     const bool full_rows = n_eff == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
@@ -346,7 +348,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                 ce[i] = (slot & 1) ? e : mid;
             }
         }
-        const bool next_is_final = ((maxlen + 1) >> 1) == 2 && p.rep_pos == 0;
+        // Next round as a compact list: always once the first or last block represents a branch (one
+        // child of every node then has the node's own representative and keeps its score), and for the
+        // centre representative in the final round (see above).
+        const bool next_is_final = p.rep_pos != 0 || ((maxlen + 1) >> 1) == 2;
+        const bool first_rule = p.rep_pos == 1;
         if (next_is_final) {
             // the branch table becomes the compact list of blocks still to be scored
             for (int i = lane; i < 2 * kb; i += 64) brt[i] = -1;
@@ -365,18 +371,24 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             int n_todo = 0;
 #pragma unroll
             for (int i = 0; i < E; ++i) {
-                const bool two = keep[i] && ce[i] - cs[i] == 2;
+                const bool two = keep[i] && ce[i] - cs[i] > 1;  // both children exist
                 const uint64_t b2 = __ballot(two);
                 if (keep[i]) {
                     const int d = dest[i];
                     ns[d] = cs[i];
                     ne[d] = ce[i];
-                    keys[2 * d] = 0u;           // left half: empty, or scored below
-                    keys[2 * d + 1] = key[i];   // right half / the node itself: score carried over
+                    // the child that shares the node's representative keeps the node's score: the left one
+                    // under the first-block rule (the node itself if it is one block long), else the right
+                    // one; the other child is empty or goes on the list (its representative: the block
+                    // at the split under the first-block rule, the block before the split otherwise)
+                    const int mid = cs[i] + ((ce[i] - cs[i]) >> 1);
+                    const int carried = (first_rule && two) ? 2 * d : 2 * d + 1;
+                    keys[carried] = key[i];
+                    keys[carried ^ 1] = 0u;
                     if (two) {
                         const int ti = n_todo + lane_prefix_count(b2);
-                        brt[ti] = cs[i] << lbk;
-                        fsl[ti] = 2 * d;
+                        brt[ti] = (first_rule ? mid : mid - 1) << lbk;
+                        fsl[ti] = carried ^ 1;
                     }
                 }
                 n_todo += __popcll(b2);
