@@ -3,7 +3,12 @@
 
 A step is one pass of the whole path over one batch of synthetic input that is already
 resident in HBM: hip_mask_estimate followed by hip_sparse_attn for one attention layer.
-Prints ONE JSON line (see DESIGN.md "Measurement" for every field).
+Prints ONE JSON line: the headline metric (`value`: whole-job tokens/s for prefill, us/step for
+decode, from wall-clock over the timed steps), per-kernel times from HIP events on the launch stream
+(`kernel_ms` mean, `kernel_ms_median`, `kernel_ms_min`), the algorithmic rates of both kernels,
+`roofline` for the slower kernel (achieved = algorithmic bytes or flops per launch / mean duration,
+against the published peak; `traffic` = HBM bytes per launch from the committed counter summaries) and
+`cpu_baseline` (the CPU oracle on a bounded sample of the same workload).
 """
 from __future__ import annotations
 

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     int cur = 0;
-    bool carry = false;  // from round 2 on, unless the centre block represents a branch
+    bool carry = false;  // set after the first iteration, unless the centre block represents a branch
     // side of a node's children that is scored in a carry round: the left one when the LAST block
     // represents (the right child ends where the node ends), the right one for FIRST
     const int side = p.rep_pos == 2 ? 0 : 1;
