@@ -291,6 +291,11 @@ def main():
                 "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": read_traffic(f"sparse_attn_{tag}")}
 
+    if roof.get("traffic"):
+        # the same kernel's HBM-side rate (counter bytes per launch / mean duration), next to the algorithmic one
+        dur = (ms_mask if roof["kernel"] == "mask_estimate" else ms_attn) * 1e-3
+        roof["traffic_GB/s"] = roof["traffic"] / dur / 1e9
+        roof["traffic_frac_hbm_peak"] = roof["traffic_GB/s"] / HBM_PEAK_GBS
     if w.q_len < w.kv_len:  # decode: one (or, for speculative decoding, a few) new rows per sequence
         metric, unit, value, hib = f"HiP decode us/step @{w.kv_len // 1024}k ctx", "us/step", ms_step * 1e3, False
     else:
