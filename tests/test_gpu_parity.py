@@ -307,3 +307,42 @@ def test_softmax_scale_extremes(sm_scale):
     U.run_case(w, 0, units=[(0, h, qb) for h in range(4) for qb in (0, 5, 20, nqb // 2, nqb - 1)], sm_scale=sm_scale)
     U.run_case(synth.scaled(synth.C3, batch=3, kv_len=9000), 0, sm_scale=sm_scale)
     U.run_case(synth.scaled(synth.C5, batch=5, kv_len=7000, ragged=(400, 7000)), 0, sm_scale=sm_scale, n_sink=4, n_window=32)
+
+
+def test_decode_step_replayed_from_a_graph():
+    # mask estimation + sparse attention captured once into a HIP graph and replayed with eager work and
+    # synchronisations in between: every replay must reproduce the eager result bit for bit (the calls
+    # allocate nothing and record no memset nodes, so a serving loop can capture them)
+    import paper_2406_09827_amd as hipattn
+    w = synth.scaled(synth.C5, batch=8, kv_len=5000, ragged=(600, 5000))
+    x = synth.make_inputs(w, device="cuda", threads=4)
+    idx = torch.empty((w.batch, w.n_q_heads, 1, w.kb), dtype=torch.int32, device="cuda")
+    out = torch.empty_like(x["Q"])
+
+    def step():
+        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                  indices=idx)
+        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+                                page_table=x["page_table"], out=out, n_sink=4, n_window=16)
+
+    step()
+    torch.cuda.synchronize()
+    idx_ref, out_ref = idx.clone(), out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                  # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for r in range(3):
+        idx.fill_(-7)
+        out.zero_()
+        x["Q"].mul_(1.0)                        # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx_ref), f"replay {r}: indices differ"
+        assert torch.equal(out, out_ref), f"replay {r}: output differs"
