@@ -346,3 +346,17 @@ def test_decode_step_replayed_from_a_graph():
         torch.cuda.synchronize()
         assert torch.equal(idx, idx_ref), f"replay {r}: indices differ"
         assert torch.equal(out, out_ref), f"replay {r}: output differs"
+
+
+@pytest.mark.parametrize("rep_pos", [1, 2])
+def test_c4_and_c2_shapes_with_first_and_last_representative(rep_pos):
+    # the list rounds of the prefill kernel (scores carried from parent to child) at the benchmark shapes:
+    # k/bk = 512 with 64-row query blocks, k/bk = 256 with 32-row blocks; and the decode carry variant at k/bk = 512
+    w = synth.scaled(synth.C4, q_len=8192 + 70, kv_len=8192 + 70, n_q_heads=4, n_kv_heads=2, integer=True)
+    nqb = w.n_query_blocks
+    U.run_case(w, 0, units=[(0, h, qb) for h in range(4) for qb in (0, 15, 16, 17, 40, 64, 65, nqb - 2, nqb - 1)], rep_pos=rep_pos)
+    w = synth.scaled(synth.C2, q_len=4096 + 40, kv_len=4096 + 40, n_q_heads=8, n_kv_heads=2, spike_every=1024)
+    nqb = w.n_query_blocks
+    U.run_case(w, 0, units=[(0, h, qb) for h in range(8) for qb in (0, 8, 9, 17, 33, 64, nqb - 2, nqb - 1)], rep_pos=rep_pos)
+    w = synth.Workload("dec_kb512", 3, 8, 2, 128, 1, 40000, 2048, 1, 4, "bf16", rho=0.9, ragged=(5000, 40000), integer=True, seed=93)
+    U.run_case(w, 0, rep_pos=rep_pos)
