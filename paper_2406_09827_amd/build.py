@@ -42,5 +42,23 @@ def build_lib(jobs: int = 8) -> str:
     return LIB
 
 
+def build_c_example() -> str:
+    """Compile the plain-C caller of the ABI (tests/c_abi/c_abi_smoke.c) with gcc against the built
+    library; the GPU tests run the binary.  Also proves that include/hipattn.h is valid C."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "c_abi", "c_abi_smoke.c")
+    exe = os.path.join(root, "tests", "c_abi", "c_abi_smoke")
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(HIPCC)))
+    cmd = ["gcc", "-std=c11", "-Wall", "-O1", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(root, "include"),
+           "-I", os.path.join(rocm, "include"), src, "-o", exe, "-L", HERE, "-lhipattn",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../../paper_2406_09827_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gcc failed on {src}:\n{r.stdout}\n{r.stderr}")
+    return exe
+
+
 if __name__ == "__main__":
     print(build_lib())
+    print(build_c_example())

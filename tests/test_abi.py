@@ -108,3 +108,12 @@ def test_binding_refuses_cpu_tensors():
     q = torch.zeros(1, 1, 16, 64)
     with pytest.raises(RuntimeError):
         hipattn.hip_mask_estimate(q, q, 8, 4, 2)
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    """The C caller under tests/c_abi compiles with gcc (-Wall -Werror) against include/hipattn.h."""
+    import subprocess
+    src = os.path.join(ROOT, "tests", "c_abi", "c_abi_smoke.c")
+    rocm_inc = "/opt/rocm/include"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"),
+                    "-I", rocm_inc, "-c", src, "-o", str(tmp_path / "c_abi_smoke.o")], check=True)

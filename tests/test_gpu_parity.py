@@ -360,3 +360,14 @@ def test_c4_and_c2_shapes_with_first_and_last_representative(rep_pos):
     U.run_case(w, 0, units=[(0, h, qb) for h in range(8) for qb in (0, 8, 9, 17, 33, 64, nqb - 2, nqb - 1)], rep_pos=rep_pos)
     w = synth.Workload("dec_kb512", 3, 8, 2, 128, 1, 40000, 2048, 1, 4, "bf16", rho=0.9, ragged=(5000, 40000), integer=True, seed=93)
     U.run_case(w, 0, rep_pos=rep_pos)
+
+
+def test_plain_c_caller_of_the_abi():
+    # tests/c_abi/c_abi_smoke.c: a C program that links the library, no Python in the call path
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "c_abi_smoke")
+    assert os.path.exists(exe), "not built: run __graft_entry__.build()"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ok" in r.stdout
