@@ -34,9 +34,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-template <int D, bool PAGED>
+// MODE 0: contiguous K/V, a (sequence, kv head) slice below 4 GB: rows are addressed by a scalar slice base
+//         plus a 32-bit lane offset (one shift-add per row instead of 64-bit vector arithmetic);
+// MODE 1: paged pool; MODE 2: contiguous, any size (64-bit row addresses).
+template <int D, int MODE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
 {
+    constexpr bool PAGED = MODE == 1, A32 = MODE == 0;
     constexpr int KS = D / 16;     // k-steps of S^T = K Q^T
     constexpr int CT = D / 32;     // 32-channel tiles of O^T
     constexpr int PITCH = D + 32;  // value tile row pitch in bf16: 64 bytes of padding per row (4 keys x 2 channel halves fill the 64 banks)
@@ -109,6 +113,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 
     const bf16_t *Kbase = (const bf16_t *)p.K, *Vbase = (const bf16_t *)p.V;
     const int64_t seq_off = (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h;  // contiguous layout: row 0 of this slice
+    // the same in every lane: as a scalar (readfirstlane) it becomes the scalar base of the row loads
+    const int64_t slice_u = ((int64_t)__builtin_amdgcn_readfirstlane((int)((seq_off * 2) >> 32)) << 32) |
+                            (uint32_t)__builtin_amdgcn_readfirstlane((int)(seq_off * 2));
+    const char *Kseq = (const char *)p.K + slice_u, *Vseq = (const char *)p.V + slice_u;
     bf16_t *vt = vt_s[wave];
     char *kt = (char *)kt_s[wave];
     uint32_t *mo = mo_s[wave];
@@ -188,8 +196,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             } else {
                 eo = seq_off + ((int64_t)off[j] << 3) + lc * 8;
             }
-            const uint4 x = *(const uint4 *)(Kbase + eo);
-            const uint4 y = *(const uint4 *)(Vbase + eo);
+            uint4 x, y;
+            if (A32) {
+                const uint32_t vo = (off[j] << 4) + (uint32_t)lc * 16u;
+                x = *(const uint4 *)(Kseq + vo);
+                y = *(const uint4 *)(Vseq + vo);
+            } else {
+                x = *(const uint4 *)(Kbase + eo);
+                y = *(const uint4 *)(Vbase + eo);
+            }
             RK[4 * j] = x.x; RK[4 * j + 1] = x.y; RK[4 * j + 2] = x.z; RK[4 * j + 3] = x.w;
             RV[4 * j] = y.x; RV[4 * j + 1] = y.y; RV[4 * j + 2] = y.z; RV[4 * j + 3] = y.w;
         }
@@ -363,13 +378,15 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     const int64_t waves = groups * per_group;
     if (waves == 0) return hipSuccess;
     dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
-    const bool paged = p.page_table != nullptr;
+    const int mode = p.page_table ? 1 : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 32) ? 0 : 2);
     if (p.d == 64) {
-        if (paged) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else hipLaunchKernelGGL((attn_mfma_kernel<64, false>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        if (mode == 1) hipLaunchKernelGGL((attn_mfma_kernel<64, 1>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<64, 0>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
     } else {
-        if (paged) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else hipLaunchKernelGGL((attn_mfma_kernel<128, false>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        if (mode == 1) hipLaunchKernelGGL((attn_mfma_kernel<128, 1>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<128, 0>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        else hipLaunchKernelGGL((attn_mfma_kernel<128, 2>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
     }
     return hipGetLastError();
 }

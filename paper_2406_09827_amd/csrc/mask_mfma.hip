@@ -13,8 +13,9 @@ bool mask_mfma_supported(const KParams &p, bool bf16)
 {
     // bf16 prefill with 1, 2 or 4 scored key rows per block (bk / b_sk) and k/bk <= 512; everything else goes to
     // the generic kernel.  The contiguous variant addresses key rows by 32-bit byte offsets from
-    // the start of a (sequence, kv head) slice.
-    const bool fits32 = p.page_table || (int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31);
+    // the start of a (sequence, kv head) slice, formed with a 24-bit multiply (row number x row pitch).
+    const bool fits32 = p.page_table || ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31) && p.max_kv_len < (1 << 24) &&
+                                         p.ks_r * 2 < (1 << 24));
     const auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     const int rows = p.bk / p.b_sk;  // key rows scored per block
     return bf16 && p.q_len > 1 && pow2(p.bk) && pow2(p.b_sk) && pow2(p.b_sq) && (rows == 1 || rows == 2 || rows == 4) &&

@@ -160,8 +160,14 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     const bool full_rows = n_eff == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
     // row 0 of this sequence / kv head (contiguous layout only)
-    const char *Kseq = (const char *)(Kbase + (int64_t)b * p.ks_b + (int64_t)hk * p.ks_h);
-    const uint32_t row_bytes = (uint32_t)p.ks_r * 2u;
+    // The slice address is the same in every lane; saying so (readfirstlane) lets the loads take it as a
+    // scalar base plus a 32-bit lane offset, which is one 24-bit multiply-add per row instead of
+    // 64-bit vector arithmetic (the launcher checks that rows and row pitch fit 24 bits).
+    const int64_t slice = ((int64_t)b * p.ks_b + (int64_t)hk * p.ks_h) * 2;  // bytes
+    const int64_t slice_u = ((int64_t)__builtin_amdgcn_readfirstlane((int)(slice >> 32)) << 32) |
+                            (uint32_t)__builtin_amdgcn_readfirstlane((int)slice);
+    const char *Kseq = (const char *)p.K + slice_u;
+    const uint32_t row_bytes = (uint32_t)p.ks_r * 2u, lc_bytes = (uint32_t)lc * 16u;
 
     // Branch-table entries one tile needs: m[0..SPL-1] for the rows this lane LOADS, m[SPL] for
     // the row it SCORES (row col of the tile).
@@ -204,7 +210,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
             x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + (n << ks), last) - tf) * p.ks_r);
         } else {
-            x = *(const uint4 *)(Kseq + ((uint32_t)min(tf + (n << ks), last) * row_bytes + (uint32_t)lc * 16u));
+            x = *(const uint4 *)(Kseq + (__umul24((uint32_t)min(tf + (n << ks), last), row_bytes) + lc_bytes));
         }
         R[4 * j] = x.x; R[4 * j + 1] = x.y; R[4 * j + 2] = x.z; R[4 * j + 3] = x.w;
     };

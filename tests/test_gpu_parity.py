@@ -371,3 +371,28 @@ def test_plain_c_caller_of_the_abi():
     r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "ok" in r.stdout
+
+
+def test_rows_four_gigabytes_apart_in_total():
+    # K and V as views whose (sequence, head) slice spans 4 GiB (1024 rows, 4 MiB row pitch): the tuned kernels
+    # switch from 32-bit lane offsets to 64-bit row addresses (attention) resp. to the generic kernel (mask);
+    # results must equal those on the packed tensors
+    import paper_2406_09827_amd as hipattn
+    w = synth.Workload("wide", 1, 2, 1, 128, 1024, 1024, 64, 32, 2, "bf16", rho=0.9, integer=True, seed=95)
+    x = synth.make_inputs(w, device="cuda", threads=1)
+    pitch = 1 << 21  # elements
+    views = {}
+    for name in ("K", "V"):
+        big = torch.empty(w.kv_len * pitch, dtype=torch.bfloat16, device="cuda")
+        v = big.as_strided((1, 1, w.kv_len, w.head_dim), (w.kv_len * pitch, w.kv_len * pitch, pitch, 1))
+        v.copy_(x[name])
+        views[name] = v
+    a = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk)
+    b = hipattn.hip_mask_estimate(x["Q"], views["K"], w.k, w.bq, w.bk)
+    assert torch.equal(a, b)
+    oa = hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], a, w.k, w.bq, w.bk)
+    ob = hipattn.hip_sparse_attn(x["Q"], views["K"], views["V"], a, w.k, w.bq, w.bk)
+    torch.cuda.synchronize()
+    assert torch.equal(oa, ob)
+    del views
+    torch.cuda.empty_cache()
