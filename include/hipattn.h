@@ -48,8 +48,8 @@ enum {
     HIP_ATTN_ENULL = -1,       /* a required pointer is NULL                                  */
     HIP_ATTN_ESHAPE = -2,      /* non-positive size, n_q_heads % n_kv_heads, q_len > kv_len,  */
                                /* negative n_sink / n_window / top_r                          */
-    HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, q_len == 1 with bq != 1,   */
-                               /* b_sq > bq, bk % b_sk != 0, unknown rep_pos                  */
+    HIP_ATTN_EBLOCK = -3,      /* k % bk != 0, bq/bk out of range, b_sq > bq, bk % b_sk != 0, */
+                               /* unknown rep_pos                                             */
     HIP_ATTN_EHEADDIM = -4,    /* head_dim not in {64, 128}                                   */
     HIP_ATTN_EDTYPE = -5,      /* dtype not HIP_ATTN_F32 / HIP_ATTN_BF16                      */
     HIP_ATTN_ETOOLARGE = -6,   /* k/bk above HIP_ATTN_MAX_KB, or bq*head_dim above the limit  */
@@ -73,7 +73,8 @@ enum {
 
 typedef struct hip_problem {
     int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64,128}                     */
-    int32_t q_len;       /* query rows per sequence: T for prefill, 1 for decode               */
+    int32_t q_len;       /* query rows per sequence: T for prefill, 1 for decode (bq is then    */
+                         /* taken as 1: the single row is its own query block)                 */
     int32_t max_kv_len;  /* T of contiguous K/V, or the largest kv_lens[b]                     */
     int32_t k, bq, bk;   /* k % bk == 0; 1 <= bq <= 64; 1 <= bk <= 16                          */
     int32_t dtype;       /* HIP_ATTN_F32 or HIP_ATTN_BF16; Q, K, V, O all have this type       */

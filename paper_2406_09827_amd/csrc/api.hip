@@ -22,7 +22,6 @@ int prepare(const hip_problem *hp, KParams &kp)
     if (p.dtype != HIP_ATTN_F32 && p.dtype != HIP_ATTN_BF16) return HIP_ATTN_EDTYPE;
     if (p.k <= 0 || p.bk <= 0 || p.bq <= 0 || p.k % p.bk) return HIP_ATTN_EBLOCK;
     if (p.bq > HIP_ATTN_MAX_BQ || p.bk > HIP_ATTN_MAX_BK) return HIP_ATTN_EBLOCK;
-    if (p.q_len == 1 && p.bq != 1) return HIP_ATTN_EBLOCK;
     if (p.b_sq < 0 || p.b_sk < 0 || p.b_sq > p.bq || (p.b_sk > 1 && p.bk % p.b_sk)) return HIP_ATTN_EBLOCK;
     if (p.rep_pos < HIP_ATTN_REP_CENTER || p.rep_pos > HIP_ATTN_REP_LAST) return HIP_ATTN_EBLOCK;
     if (p.k / p.bk > HIP_ATTN_MAX_KB) return HIP_ATTN_ETOOLARGE;
@@ -36,10 +35,12 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.batch = p.batch; kp.hq = p.n_q_heads; kp.hkv = p.n_kv_heads; kp.g = p.n_q_heads / p.n_kv_heads;
     kp.d = d; kp.q_len = p.q_len; kp.max_kv_len = p.max_kv_len;
     kp.kb = p.k / p.bk; kp.bq = p.bq; kp.bk = p.bk; kp.nqb = nqb;
+    // a single query row is a one-row query block whatever bq says: the decode kernels then serve it
+    if (p.q_len == 1) kp.bq = 1;
     kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
-    kp.b_sq = p.b_sq > 1 ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
+    kp.b_sq = (p.b_sq > 1 && p.q_len > 1) ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
     kp.top_r = p.top_r >= p.head_dim ? 0 : p.top_r;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
@@ -139,7 +140,7 @@ const char *hip_strerror(int code)
         case HIP_ATTN_OK: return "ok";
         case HIP_ATTN_ENULL: return "a required pointer is NULL";
         case HIP_ATTN_ESHAPE: return "invalid shape (sizes, head grouping, q_len > kv_len or row stride < head_dim)";
-        case HIP_ATTN_EBLOCK: return "invalid k / bq / bk (k % bk != 0, block size out of range, or decode with bq != 1)";
+        case HIP_ATTN_EBLOCK: return "invalid k / bq / bk or scoring options (k % bk != 0, block size out of range, sampling stride, representative)";
         case HIP_ATTN_EHEADDIM: return "head_dim must be 64 or 128";
         case HIP_ATTN_EDTYPE: return "dtype must be HIP_ATTN_F32 or HIP_ATTN_BF16";
         case HIP_ATTN_ETOOLARGE: return "k/bk or the number of work units exceeds the compiled maximum";

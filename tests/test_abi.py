@@ -42,7 +42,6 @@ def _ok_problem():
     (lambda p: setattr(p, "n_kv_heads", 3), -2),
     (lambda p: setattr(p, "q_len", 65), -2),
     (lambda p: (setattr(p, "k", 4096), setattr(p, "bk", 2)), -6),
-    (lambda p: (setattr(p, "q_len", 1), setattr(p, "bq", 16)), -3),
     (lambda p: (setattr(p, "page_table", 4096), setattr(p, "page_size", 3), setattr(p, "max_pages", 64)), -8),
     (lambda p: setattr(p, "q_strides", (ctypes.c_int64 * 3)(8192, 130, 2)), -7),
 ])
