@@ -62,7 +62,7 @@ def agreement(a, b):
 
 
 def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0,
-             top_r=0):
+             top_r=0, min_agreement=0.999):
     """Full comparison of one workload; returns (agreement, max output error)."""
     exact = w.integer if exact is None else exact
     x = synth.make_inputs(w, device="cuda", threads=4)
@@ -87,7 +87,7 @@ def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_windo
         agr = 1.0
     else:
         agr = agreement(idx_g, idx_ref)
-        assert agr >= 0.999, f"mask agreement {agr:.5f} < 0.999"
+        assert agr >= min_agreement, f"mask agreement {agr:.5f} < {min_agreement}"
     check_indices_valid(w, x, idx_g, units)
     # attention is compared on the GPU's own indices so that a near-tie in the mask does not
     # leak into the output comparison
