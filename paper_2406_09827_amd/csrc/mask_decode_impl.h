@@ -218,7 +218,8 @@ static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t
     } while (0)
     if (p.kb <= 128) HIPATTN_LAUNCH(4);
     else if (p.kb <= 256) HIPATTN_LAUNCH(8);
-    else HIPATTN_LAUNCH(16);
+    else if (p.kb <= 512) HIPATTN_LAUNCH(16);
+    else HIPATTN_LAUNCH(32);
 #undef HIPATTN_LAUNCH
     return hipGetLastError();
 }

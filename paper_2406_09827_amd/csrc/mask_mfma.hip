@@ -11,7 +11,7 @@ extern template hipError_t launch_mask_mfma_lb<2>(const KParams &, hipStream_t);
 
 bool mask_mfma_supported(const KParams &p, bool bf16)
 {
-    // bf16 prefill with 1, 2 or 4 scored key rows per block (bk / b_sk) and k/bk <= 512; everything else goes to
+    // bf16 prefill with 1, 2 or 4 scored key rows per block (bk / b_sk) and k/bk <= 1024; everything else goes to
     // the generic kernel.  The contiguous variant addresses key rows by 32-bit byte offsets from
     // the start of a (sequence, kv head) slice, formed with a 24-bit multiply (row number x row pitch).
     const bool fits32 = p.page_table || ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31) && p.max_kv_len < (1 << 24) &&
@@ -19,7 +19,7 @@ bool mask_mfma_supported(const KParams &p, bool bf16)
     const auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     const int rows = p.bk / p.b_sk;  // key rows scored per block
     return bf16 && p.q_len > 1 && pow2(p.bk) && pow2(p.b_sk) && pow2(p.b_sq) && (rows == 1 || rows == 2 || rows == 4) &&
-           p.bq <= 64 && p.kb <= 512 && fits32;
+           p.bq <= 64 && p.kb <= 1024 && fits32;
 }
 
 hipError_t launch_mask_mfma(const KParams &p, hipStream_t st)

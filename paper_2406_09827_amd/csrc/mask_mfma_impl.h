@@ -420,6 +420,13 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int 
 {
     mask_mfma_body<2, E, D, PAGED, LB>(p, xcd_map);
 }
+// k/bk above 512: the per-wave state alone fills the LDS of a compute unit (one wave per SIMD), and
+// the selection holds 32 keys per lane, so the one-tile kernel runs without the two-wave register cap
+template <int E, int D, bool PAGED, int LB>
+__global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q32_wide(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, E, D, PAGED, LB>(p, xcd_map);
+}
 
 template <int MT, int D, int LB>
 static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, hipStream_t st)
@@ -427,18 +434,20 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, h
     dim3 block(kThreads);
     // the page-table variant is a separate instantiation: a table read in the row-offset code
     // would otherwise put a full memory wait into the contiguous path's load pipeline
-#define HIPATTN_LAUNCH(EV)                                                                                          \
-    do {                                                                                                            \
-        if (MT == 1) {                                                                                              \
-            if (p.page_table) hipLaunchKernelGGL((mask_mfma_kernel_q32<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);   \
-            else hipLaunchKernelGGL((mask_mfma_kernel_q32<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);      \
-        } else {                                                                                                    \
-            if (p.page_table) hipLaunchKernelGGL((mask_mfma_kernel_q64<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);   \
-            else hipLaunchKernelGGL((mask_mfma_kernel_q64<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);      \
-        }                                                                                                           \
+#define HIPATTN_LAUNCH(KERNEL, EV)                                                                     \
+    do {                                                                                               \
+        if (p.page_table) hipLaunchKernelGGL((KERNEL<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);  \
+        else hipLaunchKernelGGL((KERNEL<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);           \
     } while (0)
-    if (p.kb <= 256) HIPATTN_LAUNCH(8);
-    else HIPATTN_LAUNCH(16);
+    if constexpr (MT == 1) {
+        if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
+        else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
+        else HIPATTN_LAUNCH(mask_mfma_kernel_q32_wide, 32);
+    } else {
+        if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q64, 8);
+        else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q64, 16);
+        else HIPATTN_LAUNCH(mask_mfma_kernel_q64, 32);
+    }
 #undef HIPATTN_LAUNCH
     return hipGetLastError();
 }

@@ -433,3 +433,22 @@ def test_seeded_shape_sweep_real_valued():
         total += agr
         n += 1
     assert total / n >= 0.999, f"mean agreement {total / n:.5f}"
+
+
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_k_over_bk_up_to_1024(integer):
+    # k/bk = 1024 (the maximum) and 768 on the tuned kernels: prefill with 32- and 64-row query blocks, decode
+    # contiguous and paged, last-block representative
+    w = synth.Workload("kb1024", 1, 4, 2, 128, 20000 + 30, 20000 + 30, 2048, 32, 2, "bf16", rho=0.95, spike_every=4096,
+                       integer=integer, seed=97)
+    nqb = w.n_query_blocks
+    U.run_case(w, 0, units=[(0, h, qb) for h in range(4) for qb in (0, 31, 32, 33, 70, nqb // 2, nqb - 2, nqb - 1)])
+    w = synth.Workload("kb768", 1, 2, 1, 64, 30000, 30000, 3072, 64, 4, "bf16", rho=0.95, integer=integer, seed=98)
+    nqb = w.n_query_blocks
+    U.run_case(w, 0, units=[(0, h, qb) for h in range(2) for qb in (0, 47, 48, 49, 100, nqb - 1)], rep_pos=2)
+    w = synth.Workload("kb1024_dec", 3, 4, 2, 128, 1, 50000, 2048, 1, 2, "bf16", rho=0.9, ragged=(3000, 50000),
+                       integer=integer, seed=99)
+    U.run_case(w, 0)
+    w = synth.Workload("kb1024_dec_paged", 2, 4, 1, 64, 1, 40000, 4096, 1, 4, "bf16", rho=0.9, ragged=(9000, 40000), page_size=64,
+                       integer=integer, seed=100)
+    U.run_case(w, 0, rep_pos=1)
