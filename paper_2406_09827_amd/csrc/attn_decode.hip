@@ -16,7 +16,7 @@ namespace hipattn {
 // (sequence, head), stage i of the block list goes to wave i % 4, the four partial softmax states
 // are merged through LDS.
 template <int BK, int D, int ROWS, bool PAGED, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
+__global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p, int sub_shift)
 {
     constexpr int LPR = D / 8, RPW = 64 / LPR;
     constexpr int U = ROWS / BK;  // blocks per lane group and stage: ROWS key + ROWS value row loads per lane, two stages in flight
@@ -48,7 +48,9 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
     const int nb_sink = (ns + BK - 1) / BK;
     const int win_first = (w0 / BK) * BK;
     const int nb_win = p.n_window > 0 ? (kv_len - win_first + BK - 1) / BK : 0;
-    const int n_blocks = kb + nb_sink + nb_win;
+    // key blocks of 8 or 16 rows are walked as 2 or 4 pieces of BK = 4 rows: kbv pieces in all
+    const int kbv = kb << sub_shift;
+    const int n_blocks = kbv + nb_sink + nb_win;
 
     // one stage = U blocks per lane group: BK key rows and BK value rows each, loaded
     // unconditionally (a block that does not count re-reads row 0 and gets probability 0).
@@ -59,15 +61,16 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
         for (int u = 0; u < U; ++u) {
             const int j = base + u * RPW + grp;
             int f = -1, lo = 0, hi = 0;
-            if (j < kb) {
-                f = idx[j];
+            if (j < kbv) {
+                f = idx[j >> sub_shift];
+                if (f >= 0) f += (j & ((1 << sub_shift) - 1)) * BK;
                 if (f >= kv_len) f = -1;
                 lo = p.n_sink; hi = w0;
-            } else if (j < kb + nb_sink) {
-                f = (j - kb) * BK;
+            } else if (j < kbv + nb_sink) {
+                f = (j - kbv) * BK;
                 hi = ns;
             } else if (j < n_blocks) {
-                f = win_first + (j - kb - nb_sink) * BK;
+                f = win_first + (j - kbv - nb_sink) * BK;
                 lo = w0; hi = kv_len;
             }
             first[u] = f;
@@ -194,7 +197,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p)
 
 bool attn_decode_supported(const KParams &p, bool bf16)
 {
-    return bf16 && p.q_len == 1 && p.bq == 1 && (p.bk == 1 || p.bk == 2 || p.bk == 4);
+    return bf16 && p.q_len == 1 && p.bq == 1 && (p.bk == 1 || p.bk == 2 || p.bk == 4 || p.bk == 8 || p.bk == 16);
 }
 
 hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
@@ -206,14 +209,15 @@ hipError_t launch_attn_decode(const KParams &p, hipStream_t st)
     const bool split = waves < 2048;
     dim3 grid((unsigned)(split ? waves : (waves + 3) / 4)), block(kThreads);
     const bool deep = waves < 4096, paged = p.page_table != nullptr;
+    const int sub_shift = p.bk == 8 ? 1 : p.bk == 16 ? 2 : 0;  // blocks of 8 / 16 rows as pieces of 4
 #define HIPATTN_LAUNCH(BKV, DV)                                                                        \
     do {                                                                                               \
-        if (split && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, true>), grid, block, 0, st, p);         \
-        else if (split) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, true>), grid, block, 0, st, p);            \
-        else if (deep && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, true, false>), grid, block, 0, st, p);    \
-        else if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, false, false>), grid, block, 0, st, p);            \
-        else if (paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, false>), grid, block, 0, st, p);            \
-        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, false>), grid, block, 0, st, p);                      \
+        if (split && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, true>), grid, block, 0, st, p, sub_shift);         \
+        else if (split) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, true>), grid, block, 0, st, p, sub_shift);            \
+        else if (deep && paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, true, false>), grid, block, 0, st, p, sub_shift);    \
+        else if (deep) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 8, false, false>), grid, block, 0, st, p, sub_shift);            \
+        else if (paged) hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, true, false>), grid, block, 0, st, p, sub_shift);            \
+        else hipLaunchKernelGGL((attn_decode_kernel<BKV, DV, 4, false, false>), grid, block, 0, st, p, sub_shift);                      \
     } while (0)
     if (p.d == 64) {
         if (p.bk == 1) HIPATTN_LAUNCH(1, 64);

@@ -8,7 +8,7 @@ hipError_t launch_mask_decode_carry(const KParams &p, hipStream_t st);  // mask_
 bool mask_decode_supported(const KParams &p, bool bf16)
 {
     const int rows = p.bk / p.b_sk;  // key rows scored per block
-    return bf16 && p.q_len == 1 && p.bq == 1 && (rows == 1 || rows == 2 || rows == 4) && p.kb <= 1024;
+    return bf16 && p.q_len == 1 && p.bq == 1 && (rows == 1 || rows == 2 || rows == 4 || rows == 8) && p.kb <= 1024;
 }
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)

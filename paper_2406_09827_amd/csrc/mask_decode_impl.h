@@ -250,11 +250,13 @@ template <bool CARRY> hipError_t launch_mask_decode_variant(const KParams &p, hi
     if (p.d == 64) {
         if (rows == 1) return launch_e<1, 64, CARRY>(p, st);
         if (rows == 2) return launch_e<2, 64, CARRY>(p, st);
-        return launch_e<4, 64, CARRY>(p, st);
+        if (rows == 4) return launch_e<4, 64, CARRY>(p, st);
+        return launch_e<8, 64, CARRY>(p, st);
     }
     if (rows == 1) return launch_e<1, 128, CARRY>(p, st);
     if (rows == 2) return launch_e<2, 128, CARRY>(p, st);
-    return launch_e<4, 128, CARRY>(p, st);
+    if (rows == 4) return launch_e<4, 128, CARRY>(p, st);
+    return launch_e<8, 128, CARRY>(p, st);
 }
 
 }  // namespace hipattn

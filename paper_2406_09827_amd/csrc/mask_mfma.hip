@@ -8,17 +8,18 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
 extern template hipError_t launch_mask_mfma_lb<0>(const KParams &, hipStream_t);
 extern template hipError_t launch_mask_mfma_lb<1>(const KParams &, hipStream_t);
 extern template hipError_t launch_mask_mfma_lb<2>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_mfma_lb<3>(const KParams &, hipStream_t);
 
 bool mask_mfma_supported(const KParams &p, bool bf16)
 {
-    // bf16 prefill with 1, 2 or 4 scored key rows per block (bk / b_sk) and k/bk <= 1024; everything else goes to
+    // bf16 prefill with 1, 2, 4 (or, at head dim 128, 8) scored key rows per block (bk / b_sk) and k/bk <= 1024; everything else goes to
     // the generic kernel.  The contiguous variant addresses key rows by 32-bit byte offsets from
     // the start of a (sequence, kv head) slice, formed with a 24-bit multiply (row number x row pitch).
     const bool fits32 = p.page_table || ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31) && p.max_kv_len < (1 << 24) &&
                                          p.ks_r * 2 < (1 << 24));
     const auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     const int rows = p.bk / p.b_sk;  // key rows scored per block
-    return bf16 && p.q_len > 1 && pow2(p.bk) && pow2(p.b_sk) && pow2(p.b_sq) && (rows == 1 || rows == 2 || rows == 4) &&
+    return bf16 && p.q_len > 1 && pow2(p.bk) && pow2(p.b_sk) && pow2(p.b_sq) && (rows == 1 || rows == 2 || rows == 4 || (rows == 8 && p.d == 128)) &&
            p.bq <= 64 && p.kb <= 1024 && fits32;
 }
 
@@ -27,7 +28,8 @@ hipError_t launch_mask_mfma(const KParams &p, hipStream_t st)
     const int rows = p.bk / p.b_sk;
     if (rows == 1) return launch_mask_mfma_lb<0>(p, st);
     if (rows == 2) return launch_mask_mfma_lb<1>(p, st);
-    return launch_mask_mfma_lb<2>(p, st);
+    if (rows == 4) return launch_mask_mfma_lb<2>(p, st);
+    return launch_mask_mfma_lb<3>(p, st);
 }
 
 }  // namespace hipattn

@@ -259,6 +259,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         v = max_half_swap(v);
         if (LB >= 1) v = fmaxf(v, dpp_f<0xB1>(v));  // lane ^ 1
         if (LB >= 2) v = fmaxf(v, dpp_f<0x4E>(v));  // lane ^ 2
+        if (LB >= 3) v = fmaxf(v, dpp_f<0x141>(v)); // lane i <-> 7 - i of each 8 lanes: the other quad (quads are uniform by now)
         const int sl = slot < 0 ? ~slot : slot;
         // (in the final round the keys are preset and an empty entry names no slot)
         if (hh == 0 && (col & (BK - 1)) == 0 && (slot >= 0 || !final_mode)) keys[sl] = slot < 0 ? 0u : score_key(v);
@@ -461,8 +462,11 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     const int64_t units = groups * per_group;
     if (units == 0) return hipSuccess;
     dim3 grid((unsigned)((units + 3) / 4));
-    if ((p.bq + p.b_sq - 1) / p.b_sq <= 32) return p.d == 64 ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st);
-    return p.d == 64 ? launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, st);
+    const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
+    if constexpr (LB <= 2) {  // (with 64 channels a lane loads 4 rows of a tile, fewer than an 8-row block)
+        if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, st);
+    }
+    return one_tile ? launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, st);
 }
 
 }  // namespace hipattn

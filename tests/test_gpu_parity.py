@@ -452,3 +452,21 @@ def test_k_over_bk_up_to_1024(integer):
     w = synth.Workload("kb1024_dec_paged", 2, 4, 1, 64, 1, 40000, 4096, 1, 4, "bf16", rho=0.9, ragged=(9000, 40000), page_size=64,
                        integer=integer, seed=100)
     U.run_case(w, 0, rep_pos=1)
+
+
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_blocks_of_8_and_16_keys(integer):
+    # bk = 8 (8 scored rows per block) and bk = 16 with b_sk = 2 on the tuned kernels: prefill at head dim 128,
+    # decode (mask with 8 rows per block; attention walks the blocks as pieces of 4 rows)
+    w = synth.Workload("bk8", 1, 4, 2, 128, 6000 + 50, 6000 + 50, 1024, 32, 8, "bf16", rho=0.95, spike_every=1024,
+                       integer=integer, seed=101)
+    nqb = w.n_query_blocks
+    units = [(0, h, qb) for h in range(4) for qb in (0, 31, 32, 33, 70, nqb // 2, nqb - 2, nqb - 1)]
+    U.run_case(w, 0, units=units)
+    U.run_case(synth.scaled(w, bk=16, k=2048, bq=64), 0, units=[(0, h, qb) for h in range(4) for qb in (0, 15, 16, 40, nqb // 2 - 1)],
+               b_sk=2, rep_pos=2, n_sink=8, n_window=40)
+    wd = synth.Workload("bk8_dec", 4, 4, 2, 128, 1, 30000, 2048, 1, 8, "bf16", rho=0.9, ragged=(3000, 30000),
+                        integer=integer, seed=102)
+    U.run_case(wd, 0, n_sink=5, n_window=21)
+    U.run_case(synth.scaled(wd, bk=16, k=4096, page_size=64, head_dim=64), 0, b_sk=2, rep_pos=1, n_window=50)
+    U.run_case(synth.scaled(wd, batch=700, n_q_heads=2, n_kv_heads=1, kv_len=3000, ragged=(400, 3000), k=256), 0)   # wave-per-problem variants
