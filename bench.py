@@ -199,6 +199,8 @@ def main():
                     help="decode only: estimate the mask every R-th step and reuse it in between (Alg. 2's mask "
                          "refresh period); combine with --n-window >= R so that the newest keys stay attended")
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (a multiple of its bk)")
+    ap.add_argument("--bk", type=int, default=0, help="override the workload's key block size")
+    ap.add_argument("--bq", type=int, default=0, help="override the workload's query block size")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this GPU sustains on a 1 GiB device copy and on back-to-back bf16 MFMAs")
     ap.add_argument("--dense-yardstick", action="store_true",
@@ -221,6 +223,10 @@ def main():
                          name=f"{w.name}_T{args.seq_len}")
     if args.k > 0:
         w = synth.scaled(w, k=args.k, name=f"{w.name}_k{args.k}")
+    if args.bk > 0:
+        w = synth.scaled(w, bk=args.bk, name=f"{w.name}_bk{args.bk}")
+    if args.bq > 0:
+        w = synth.scaled(w, bq=args.bq, name=f"{w.name}_bq{args.bq}")
     flags = hipattn.FORCE_GENERIC if args.generic else 0
     t0 = time.perf_counter()
     x = synth.make_inputs(w, device="cuda", threads=16)
@@ -282,7 +288,7 @@ def main():
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
     attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
-    tag = args.workload if args.seq_len == 0 and args.k == 0 else "none"   # counter summaries exist for the named workloads only
+    tag = args.workload if args.seq_len == 0 and args.k == 0 and args.bk == 0 and args.bq == 0 else "none"   # counter summaries exist for the named workloads only
     if ms_mask >= ms_attn:
         roof = {"kernel": "mask_estimate", "bound": "hbm", "achieved": mask_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{tag}")}
