@@ -19,6 +19,9 @@ bool mask_mfma_supported(const KParams &p, bool bf16)
                                          p.ks_r * 2 < (1 << 24));
     const auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     const int rows = p.bk / p.b_sk;  // key rows scored per block
+    // 1024 branch slots with one query tile: list rounds pack (slot, block index) into one word, 21 bits of index
+    const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
+    if (p.kb > 256 && p.kb <= 512 && one_tile && (p.max_kv_len + p.bk - 1) / p.bk >= (1 << 21)) return false;
     return bf16 && p.q_len > 1 && pow2(p.bk) && pow2(p.b_sk) && pow2(p.b_sq) && (rows == 1 || rows == 2 || rows == 4 || (rows == 8 && p.d == 128)) &&
            p.bq <= 64 && p.kb <= 1024 && fits32;
 }

@@ -61,7 +61,12 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     __shared__ uint32_t keys_s[4][NB];
     __shared__ int nds[4][NB / 2], nde[4][NB / 2];                   // node ranges [s, e) in key blocks
     __shared__ __attribute__((aligned(16))) int brt_s[4][NB];        // per branch slot: first key of its centre block, -1 = empty
-    __shared__ int fsl_s[4][NB / 2];                                 // final round: slot of the i-th block still to be scored
+    // List rounds: slot of the i-th block still to be scored.  With 1024 branch slots and one query tile the
+    // slot is packed into the list entry instead (slot << 21 | block index; the launcher checks that block
+    // indices fit 21 bits): without this array the workgroup's LDS is 80 KB and two workgroups share a
+    // compute unit.
+    constexpr bool PACK = E == 16 && MT == 1;
+    __shared__ int fsl_s[PACK ? 1 : 4][PACK ? 1 : NB / 2];
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -124,7 +129,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     }
 
     uint32_t *keys = keys_s[wave];
-    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave], *fsl = fsl_s[wave];
+    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave], *fsl = fsl_s[PACK ? 0 : wave];
     char *tile_s = (char *)tile_buf[wave];
 
     // the two branches of node [s, e): left [s, mid) (empty for a one-block node), right [mid, e);
@@ -185,7 +190,15 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         }
         mt_.m[SPL] = brt[(tile * 32 + col) >> LB];
         const int ti = (tile * 32 + col) >> LB;
-        mt_.sl = final_mode ? fsl[min(ti, NB / 2 - 1)] : ti;  // (entries past the list are never used)
+        if (PACK) {
+            mt_.sl = final_mode ? mt_.m[SPL] >> 21 : ti;
+            if (final_mode) {
+#pragma unroll
+                for (int i = 0; i <= SPL; ++i) mt_.m[i] = mt_.m[i] < 0 ? -1 : (mt_.m[i] & 0x1fffff) << lbk;
+            }
+        } else {
+            mt_.sl = final_mode ? fsl[min(ti, NB / 2 - 1)] : ti;  // (entries past the list are never used)
+        }
     };
 
     // Row info of a tile from the metadata read earlier: t = key position of this lane's scored row,
@@ -394,8 +407,9 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     keys[carried ^ 1] = 0u;
                     if (two) {
                         const int ti = n_todo + lane_prefix_count(b2);
-                        brt[ti] = (first_rule ? mid : mid - 1) << lbk;
-                        fsl[ti] = carried ^ 1;
+                        const int blk = first_rule ? mid : mid - 1;
+                        if (PACK) brt[ti] = ((carried ^ 1) << 21) | blk;
+                        else { brt[ti] = blk << lbk; fsl[ti] = carried ^ 1; }
                     }
                 }
                 n_todo += __popcll(b2);
