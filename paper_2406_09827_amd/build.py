@@ -18,7 +18,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-fno-h
 
 
 def sources():
-    return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+    """Kernel sources, the translation units with the most template instantiations first (they take the
+    longest, so starting them first shortens the parallel build)."""
+    heavy = ("mask_decode", "mask_mfma_bk", "attn_decode", "attn_mfma")
+    names = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
+    return sorted(names, key=lambda n: next((i for i, h in enumerate(heavy) if n.startswith(h)), len(heavy)))
 
 
 def _compile(src: str) -> str:

@@ -1,9 +1,12 @@
-// Decode mask estimation: the default variant (centre representative) and the dispatch.
+// Decode mask estimation: dispatch over the variants (each instantiated in its own translation unit).
 #include "mask_decode_impl.h"
 
 namespace hipattn {
 
-hipError_t launch_mask_decode_carry(const KParams &p, hipStream_t st);  // mask_decode_carry.hip
+extern template hipError_t launch_mask_decode_variant<false, 64>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<false, 128>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<true, 64>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<true, 128>(const KParams &, hipStream_t);
 
 bool mask_decode_supported(const KParams &p, bool bf16)
 {
@@ -13,7 +16,9 @@ bool mask_decode_supported(const KParams &p, bool bf16)
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
 {
-    return p.rep_pos != 0 ? launch_mask_decode_carry(p, st) : launch_mask_decode_variant<false>(p, st);
+    // first / last representative: the variant that carries a node's score to the child sharing its representative
+    if (p.rep_pos != 0) return p.d == 64 ? launch_mask_decode_variant<true, 64>(p, st) : launch_mask_decode_variant<true, 128>(p, st);
+    return p.d == 64 ? launch_mask_decode_variant<false, 64>(p, st) : launch_mask_decode_variant<false, 128>(p, st);
 }
 
 }  // namespace hipattn

@@ -242,21 +242,15 @@ static hipError_t launch_e(const KParams &p, hipStream_t st)
     return launch_r<BK, D, 16, false, CARRY>(p, grid, 0, st);
 }
 
-// One translation unit per variant instantiates this.
-template <bool CARRY> hipError_t launch_mask_decode_variant(const KParams &p, hipStream_t st)
+// One translation unit per (variant, head dim) instantiates this.
+template <bool CARRY, int D> hipError_t launch_mask_decode_variant(const KParams &p, hipStream_t st)
 {
     if ((int64_t)p.batch * p.hq == 0) return hipSuccess;
     const int rows = p.bk / p.b_sk;
-    if (p.d == 64) {
-        if (rows == 1) return launch_e<1, 64, CARRY>(p, st);
-        if (rows == 2) return launch_e<2, 64, CARRY>(p, st);
-        if (rows == 4) return launch_e<4, 64, CARRY>(p, st);
-        return launch_e<8, 64, CARRY>(p, st);
-    }
-    if (rows == 1) return launch_e<1, 128, CARRY>(p, st);
-    if (rows == 2) return launch_e<2, 128, CARRY>(p, st);
-    if (rows == 4) return launch_e<4, 128, CARRY>(p, st);
-    return launch_e<8, 128, CARRY>(p, st);
+    if (rows == 1) return launch_e<1, D, CARRY>(p, st);
+    if (rows == 2) return launch_e<2, D, CARRY>(p, st);
+    if (rows == 4) return launch_e<4, D, CARRY>(p, st);
+    return launch_e<8, D, CARRY>(p, st);
 }
 
 }  // namespace hipattn
