@@ -198,6 +198,8 @@ def main():
     ap.add_argument("--refresh-period", type=int, default=1,
                     help="decode only: estimate the mask every R-th step and reuse it in between (Alg. 2's mask "
                          "refresh period); combine with --n-window >= R so that the newest keys stay attended")
+    ap.add_argument("--q-len", type=int, default=0,
+                    help="query rows per sequence, placed at the end of the context (chunked prefill, speculative decoding)")
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (a multiple of its bk)")
     ap.add_argument("--bk", type=int, default=0, help="override the workload's key block size")
     ap.add_argument("--bq", type=int, default=0, help="override the workload's query block size")
@@ -221,6 +223,8 @@ def main():
     if args.seq_len > 0:
         w = synth.scaled(w, kv_len=args.seq_len, q_len=args.seq_len if w.q_len == w.kv_len else w.q_len,
                          name=f"{w.name}_T{args.seq_len}")
+    if args.q_len > 0:
+        w = synth.scaled(w, q_len=args.q_len, name=f"{w.name}_q{args.q_len}")
     if args.k > 0:
         w = synth.scaled(w, k=args.k, name=f"{w.name}_k{args.k}")
     if args.bk > 0:
@@ -288,7 +292,7 @@ def main():
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
     attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
-    tag = args.workload if args.seq_len == 0 and args.k == 0 and args.bk == 0 and args.bq == 0 else "none"   # counter summaries exist for the named workloads only
+    tag = args.workload if args.seq_len == 0 and args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 else "none"   # counter summaries exist for the named workloads only
     if ms_mask >= ms_attn:
         roof = {"kernel": "mask_estimate", "bound": "hbm", "achieved": mask_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": mask_gbs / HBM_PEAK_GBS, "traffic": read_traffic(f"mask_estimate_{tag}")}

@@ -45,7 +45,9 @@ __device__ __forceinline__ float max_half_swap(float v)
 
 // MT = 32-row query tiles (1 or 2), E = branch slots / 64, D = head dim,
 // LB = log2(key rows scored per block) = log2(bk / b_sk)
-template <int MT, int E, int D, bool PAGED, int LB>
+// SPLIT: the workgroup takes ONE work item; its four waves share the node state, score a quarter of the tiles
+// each and run the selection redundantly (for launches with too few work items to fill the GPU wave by wave)
+template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
     constexpr int NB = 64 * E;     // branch slots
@@ -58,19 +60,21 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     constexpr int ROWB = D * 2;    // bytes per row
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * NLD)));
     static_assert(SPL >= 1, "bk too large for this kernel");
-    __shared__ uint32_t keys_s[4][NB];
-    __shared__ int nds[4][NB / 2], nde[4][NB / 2];                   // node ranges [s, e) in key blocks
-    __shared__ __attribute__((aligned(16))) int brt_s[4][NB];        // per branch slot: first key of its centre block, -1 = empty
+    constexpr int NC = SPLIT ? 1 : 4;  // copies of the per-work-item state
+    __shared__ uint32_t keys_s[NC][NB];
+    __shared__ int nds[NC][NB / 2], nde[NC][NB / 2];                   // node ranges [s, e) in key blocks
+    __shared__ __attribute__((aligned(16))) int brt_s[NC][NB];        // per branch slot: first key of its centre block, -1 = empty
     // List rounds: slot of the i-th block still to be scored.  With 1024 branch slots and one query tile the
     // slot is packed into the list entry instead (slot << 21 | block index; the launcher checks that block
     // indices fit 21 bits): without this array the workgroup's LDS is 80 KB and two workgroups share a
     // compute unit.
     constexpr bool PACK = E == 16 && MT == 1;
-    __shared__ int fsl_s[PACK ? 1 : 4][PACK ? 1 : NB / 2];
+    __shared__ int fsl_s[PACK ? 1 : NC][PACK ? 1 : NB / 2];
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
+    const int own = SPLIT ? 0 : wave;  // which copy of the state
 
     // ---- which (sequence, head, query block) this wave owns.  With `xcd_map` the workgroups an
     // XCD receives (blockIdx.x % 8) all read the same KV head; query blocks go from the longest
@@ -80,11 +84,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     int64_t group, o;
     if (xcd_map) {
         const int64_t bid = blockIdx.x;
-        const int64_t seq = (bid >> 3) * 4 + wave;
+        const int64_t seq = SPLIT ? (bid >> 3) : (bid >> 3) * 4 + wave;
         group = (bid & 7) + 8 * (seq / per_group);
         o = seq % per_group;
     } else {
-        const int64_t lin = (int64_t)blockIdx.x * 4 + wave;
+        const int64_t lin = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
         group = lin / per_group;
         o = lin % per_group;
     }
@@ -128,8 +132,12 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         }
     }
 
-    uint32_t *keys = keys_s[wave];
-    int *ns = nds[wave], *ne = nde[wave], *brt = brt_s[wave], *fsl = fsl_s[PACK ? 0 : wave];
+    uint32_t *keys = keys_s[own];
+    int *ns = nds[own], *ne = nde[own], *brt = brt_s[own], *fsl = fsl_s[PACK ? 0 : own];
+    // the waves of a work item meet here (SPLIT); otherwise the point only orders one wave's LDS traffic
+    auto sync_unit = [&]() __attribute__((always_inline)) {
+        if (SPLIT) __syncthreads(); else wave_lds_sync();
+    };
     char *tile_s = (char *)tile_buf[wave];
 
     // the two branches of node [s, e): left [s, mid) (empty for a one-block node), right [mid, e);
@@ -141,7 +149,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         brt[2 * j + 1] = rep_block(mid, e, p.rep_pos) << lbk;
     };
     for (int i = lane; i < NB; i += 64) { keys[i] = 0; brt[i] = -1; }
-    wave_lds_sync();
+    sync_unit();
     {
         const int a = Tb / kb, r = Tb % kb;
         for (int j = lane; j < kb; j += 64) {
@@ -150,7 +158,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             put_branches(j, s, e);
         }
     }
-    wave_lds_sync();
+    sync_unit();
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
     int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
@@ -310,24 +318,27 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         // (it is then loaded and scored again, which rewrites the same keys), because a load that is
         // issued on some paths only makes the compiler wait for ALL outstanding loads before it
         // touches a staged register, and that exposes the full memory latency in every tile.
-        const int nt = __builtin_amdgcn_readfirstlane(n_tiles);
+        // With SPLIT, wave w takes tiles w, w + 4, ...: tile_of(i) is the i-th tile of this wave.
+        const int nt_all = __builtin_amdgcn_readfirstlane(n_tiles);
+        const int nt = SPLIT ? (nt_all > wave ? (nt_all - wave + 3) >> 2 : 0) : nt_all;
         if (nt > 0) {
             const int last_tile = nt - 1;
+            auto tile_of = [&](int i) __attribute__((always_inline)) { return SPLIT ? wave + 4 * min(i, last_tile) : min(i, last_tile); };
             stage_t R0, R1;  // one vector value each, so the staged rows stay in registers
             meta_t m0, m1;
             int t0, s0, t1, s1;
-            read_meta(0, m0);
-            read_meta(min(1, last_tile), m1);
+            read_meta(tile_of(0), m0);
+            read_meta(tile_of(1), m1);
             load_rows(m0, R0, t0, s0);
-            read_meta(min(2, last_tile), m0);
+            read_meta(tile_of(2), m0);
             load_rows(m1, R1, t1, s1);
-            read_meta(min(3, last_tile), m1);
+            read_meta(tile_of(3), m1);
             // tile 0 goes into the LDS tile; from then on the tile after the one being multiplied is
             // written to LDS (and the loads of the tile three ahead are issued) between the multiplies
             int tcur = t0, scur = s0;
             park(R0);
             load_rows(m0, R0, t0, s0);
-            read_meta(min(4, last_tile), m0);
+            read_meta(tile_of(4), m0);
             wave_lds_sync();
             for (int tile = 0; tile < nt; tile += 2) {
                 // here: tile `tile` is in LDS (its row info in tcur/scur), R1 holds tile+1, R0 tile+2,
@@ -335,18 +346,19 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                 acc_t A;
                 const int tn = t1, sn = s1;
                 multiply_and_restage(A, R1, m1, t1, s1);
-                read_meta(min(tile + 5, last_tile), m1);
+                read_meta(tile_of(tile + 5), m1);
                 wave_lds_sync();
                 score_finish(A, tcur, scur);
                 // tile+1 is in LDS, R0 holds tile+2, R1 tile+3
                 acc_t B;
                 tcur = t0; scur = s0;
                 multiply_and_restage(B, R0, m0, t0, s0);
-                read_meta(min(tile + 6, last_tile), m0);
+                read_meta(tile_of(tile + 6), m0);
                 wave_lds_sync();
                 score_finish(B, tn, sn);
             }
         }
+        sync_unit();  // every score of the round is in place
 
         // ordered top-kb selection; survivors are compacted in place: every lane first reads the
         // parents of the slots it keeps, then (after all reads) writes the new nodes and their branches
@@ -377,7 +389,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             // the branch table becomes the compact list of blocks still to be scored
             for (int i = lane; i < 2 * kb; i += 64) brt[i] = -1;
         }
-        wave_lds_sync();
+        sync_unit();
         if (!next_is_final) {
 #pragma unroll
             for (int i = 0; i < E; ++i) {
@@ -418,7 +430,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             final_mode = true;
             n_tiles = (n_todo * BK + 31) >> 5;
         }
-        wave_lds_sync();
+        sync_unit();
     }
 
     for (int j = lane; j < kb; j += 64) out[j] = ns[j] << lbk;
@@ -435,6 +447,17 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int 
 {
     mask_mfma_body<2, E, D, PAGED, LB>(p, xcd_map);
 }
+// Few work items: a workgroup per work item (see SPLIT above)
+template <int E, int D, bool PAGED, int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void mask_mfma_kernel_q32_split(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, E, D, PAGED, LB, true>(p, xcd_map);
+}
+template <int E, int D, bool PAGED, int LB>
+__global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64_split(KParams p, int xcd_map)
+{
+    mask_mfma_body<2, E, D, PAGED, LB, true>(p, xcd_map);
+}
 // k/bk above 512: the per-wave state alone fills the LDS of a compute unit (one wave per SIMD), and
 // the selection holds 32 keys per lane, so the one-tile kernel runs without the two-wave register cap
 template <int E, int D, bool PAGED, int LB>
@@ -444,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q32_wide(KParams p,
 }
 
 template <int MT, int D, int LB>
-static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, hipStream_t st)
+static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, bool split, hipStream_t st)
 {
     dim3 block(kThreads);
     // the page-table variant is a separate instantiation: a table read in the row-offset code
@@ -454,7 +477,15 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, h
         if (p.page_table) hipLaunchKernelGGL((KERNEL<EV, D, true, LB>), grid, block, 0, st, p, xcd_map);  \
         else hipLaunchKernelGGL((KERNEL<EV, D, false, LB>), grid, block, 0, st, p, xcd_map);           \
     } while (0)
-    if constexpr (MT == 1) {
+    if (split) {
+        if constexpr (MT == 1) {
+            if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32_split, 8);
+            else HIPATTN_LAUNCH(mask_mfma_kernel_q32_split, 16);
+        } else {
+            if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q64_split, 8);
+            else HIPATTN_LAUNCH(mask_mfma_kernel_q64_split, 16);
+        }
+    } else if constexpr (MT == 1) {
         if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
         else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
         else HIPATTN_LAUNCH(mask_mfma_kernel_q32_wide, 32);
@@ -472,15 +503,18 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
 {
     const int64_t groups = (int64_t)p.batch * p.hkv;
     const int64_t per_group = (int64_t)p.g * p.nqb;
-    const int xcd_map = (groups % 8 == 0 && per_group % 4 == 0) ? 1 : 0;
     const int64_t units = groups * per_group;
     if (units == 0) return hipSuccess;
-    dim3 grid((unsigned)((units + 3) / 4));
+    // Too few work items to fill the GPU one wave each (2048 wave slots at two waves per SIMD): a
+    // workgroup per work item, four waves sharing its tiles.
+    const bool split = units <= 1024 && p.kb <= 512;
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
+    dim3 grid((unsigned)(split ? units : (units + 3) / 4));
     const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
     if constexpr (LB <= 2) {  // (with 64 channels a lane loads 4 rows of a tile, fewer than an 8-row block)
-        if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, st);
+        if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, split, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, split, st);
     }
-    return one_tile ? launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, st);
+    return one_tile ? launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, split, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, split, st);
 }
 
 }  // namespace hipattn
