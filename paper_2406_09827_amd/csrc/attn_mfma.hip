@@ -37,7 +37,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // MODE 0: contiguous K/V, a (sequence, kv head) slice below 4 GB: rows are addressed by a scalar slice base
 //         plus a 32-bit lane offset (one shift-add per row instead of 64-bit vector arithmetic);
 // MODE 1: paged pool; MODE 2: contiguous, any size (64-bit row addresses).
-template <int D, int MODE>
+// SPLIT: the workgroup takes ONE work item; wave w walks key tiles w, w + 4, ... with its own softmax state and the
+//        four states are merged through LDS at the end (for launches with too few work items to fill the GPU).
+template <int D, int MODE, bool SPLIT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void attn_mfma_kernel(KParams p, int log_bk, int mtn, int xcd_map)
 {
     constexpr bool PAGED = MODE == 1, A32 = MODE == 0;
@@ -54,7 +56,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     __shared__ __attribute__((aligned(16))) int tk_s[4][2][32];
     __shared__ __attribute__((aligned(16))) uint32_t mo_s[4][32];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
 
@@ -64,11 +66,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     int64_t group, o;
     if (xcd_map) {  // blockIdx.x % 8 = XCD: all work of a KV head goes to one XCD's L2
         const int64_t bid = blockIdx.x;
-        const int64_t seq = (bid >> 3) * 4 + wave;
+        const int64_t seq = SPLIT ? (bid >> 3) : (bid >> 3) * 4 + wave;
         group = (bid & 7) + 8 * (seq / per_group);
         o = seq % per_group;
     } else {
-        const int64_t lin = (int64_t)blockIdx.x * 4 + wave;
+        const int64_t lin = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
         group = lin / per_group;
         o = lin % per_group;
     }
@@ -211,10 +213,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         return flags;
     };
 
+    // this wave's tiles: all of them, or every fourth one (SPLIT)
+    const int nt = SPLIT ? (n_tiles > wave ? (n_tiles - wave + 3) >> 2 : 0) : n_tiles;
+    auto tile_of = [&](int i) __attribute__((always_inline)) { return SPLIT ? wave + 4 * i : i; };
     stage_t RK, RV;
-    int flags_next = fetch(0, index_entry(0), RK, RV, tk_s[wave][0]);
-    int first_next = index_entry(1);
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    int flags_next = 0, first_next = -1;
+    if (nt > 0) {
+        flags_next = fetch(tile_of(0), index_entry(tile_of(0)), RK, RV, tk_s[wave][0]);
+        first_next = index_entry(tile_of(1));
+    }
+    for (int tile = 0; tile < nt; ++tile) {
         const int flags = flags_next;
         const int *tk = tk_s[wave][tile & 1];
         // registers -> LDS: key tile swizzled (chunk lc of row r at slot lc ^ (r % CPR)), value tile padded
@@ -224,9 +232,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             *(uint4 *)(kt + r * ROWB + ((lc ^ (r & (CPR - 1))) << 4)) = make_uint4(RK[4 * j], RK[4 * j + 1], RK[4 * j + 2], RK[4 * j + 3]);
             *(uint4 *)(vt + r * PITCH + lc * 8) = make_uint4(RV[4 * j], RV[4 * j + 1], RV[4 * j + 2], RV[4 * j + 3]);
         }
-        if (tile + 1 < n_tiles) {
-            flags_next = fetch(tile + 1, first_next, RK, RV, tk_s[wave][(tile + 1) & 1]);
-            first_next = index_entry(tile + 2);
+        if (tile + 1 < nt) {
+            flags_next = fetch(tile_of(tile + 1), first_next, RK, RV, tk_s[wave][(tile + 1) & 1]);
+            first_next = index_entry(tile_of(tile + 2));
         }
         wave_lds_sync();
 
@@ -339,6 +347,44 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         wave_lds_sync();  // the tiles are consumed before the next iteration overwrites them
     }
 
+    if (SPLIT) {
+        // Waves 1-3 leave their state (running reference, partial sum, accumulators) in their own tile
+        // buffers, lane-contiguous; wave 0 folds them into its own: with m = max of the references, every
+        // state is rescaled by 2^(m_w - m) before it is added (the usual merge of online-softmax states).
+        constexpr int HALF = (CT / 2) * 16 * 64;  // floats of the first CT/2 accumulators = the key tile's size
+        float *sk = (float *)kt_s[wave], *sv = (float *)vt_s[wave];
+        if (wave != 0) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float *dst = ct < CT / 2 ? sk + (ct * 16 + r) * 64 : sv + ((ct - CT / 2) * 16 + r) * 64;
+                    dst[lane] = oacc[ct][r];
+                }
+            sv[HALF + lane] = m_run;
+            sv[HALF + 64 + lane] = l_run;
+        }
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float *ok = (const float *)kt_s[w], *ov = (const float *)vt_s[w];
+            const float m_w = ov[HALF + lane], l_w = ov[HALF + 64 + lane];
+            const float m_new = fmaxf(m_run, m_w);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float a = __builtin_amdgcn_exp2f(m_run - m_safe), bw = __builtin_amdgcn_exp2f(m_w - m_safe);
+            l_run = l_run * a + l_w * bw;
+            m_run = m_new;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float *src = ct < CT / 2 ? ok + (ct * 16 + r) * 64 : ov + ((ct - CT / 2) * 16 + r) * 64;
+                    oacc[ct][r] = oacc[ct][r] * a + src[lane] * bw;
+                }
+        }
+    }
+
     // ---- normalise, transpose through LDS, coalesced store
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -374,20 +420,25 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     const int mtn = (p.bq + 31) / 32;
     const int64_t groups = (int64_t)p.batch * p.hkv;
     const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
-    const int xcd_map = (groups % 8 == 0 && per_group % 4 == 0) ? 1 : 0;
     const int64_t waves = groups * per_group;
     if (waves == 0) return hipSuccess;
-    dim3 grid((unsigned)((waves + 3) / 4)), block(kThreads);
+    // too few work items to fill the GPU one wave each: a workgroup per work item, four waves share its key tiles
+    const bool split = waves <= 1024;
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
+    dim3 grid((unsigned)(split ? waves : (waves + 3) / 4)), block(kThreads);
     const int mode = p.page_table ? 1 : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 32) ? 0 : 2);
+#define HIPATTN_LAUNCH(DV, SP)                                                                                  \
+    do {                                                                                                        \
+        if (mode == 1) hipLaunchKernelGGL((attn_mfma_kernel<DV, 1, SP>), grid, block, 0, st, p, log_bk, mtn, xcd_map);      \
+        else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<DV, 0, SP>), grid, block, 0, st, p, log_bk, mtn, xcd_map); \
+        else hipLaunchKernelGGL((attn_mfma_kernel<DV, 2, SP>), grid, block, 0, st, p, log_bk, mtn, xcd_map);                \
+    } while (0)
     if (p.d == 64) {
-        if (mode == 1) hipLaunchKernelGGL((attn_mfma_kernel<64, 1>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<64, 0>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else hipLaunchKernelGGL((attn_mfma_kernel<64, 2>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        if (split) HIPATTN_LAUNCH(64, true); else HIPATTN_LAUNCH(64, false);
     } else {
-        if (mode == 1) hipLaunchKernelGGL((attn_mfma_kernel<128, 1>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<128, 0>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
-        else hipLaunchKernelGGL((attn_mfma_kernel<128, 2>), grid, block, 0, st, p, log_bk, mtn, xcd_map);
+        if (split) HIPATTN_LAUNCH(128, true); else HIPATTN_LAUNCH(128, false);
     }
+#undef HIPATTN_LAUNCH
     return hipGetLastError();
 }
 
