@@ -422,8 +422,8 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
     const int64_t waves = groups * per_group;
     if (waves == 0) return hipSuccess;
-    // too few work items to fill the GPU one wave each: a workgroup per work item, four waves share its key tiles
-    const bool split = waves <= 1024;
+    // few work items (a quarter of the GPU's wave slots or less): a workgroup per work item, four waves share its key tiles
+    const bool split = waves <= 512;
     const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
     dim3 grid((unsigned)(split ? waves : (waves + 3) / 4)), block(kThreads);
     const int mode = p.page_table ? 1 : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 32) ? 0 : 2);

@@ -505,9 +505,9 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     const int64_t per_group = (int64_t)p.g * p.nqb;
     const int64_t units = groups * per_group;
     if (units == 0) return hipSuccess;
-    // Too few work items to fill the GPU one wave each (2048 wave slots at two waves per SIMD): a
-    // workgroup per work item, four waves sharing its tiles.
-    const bool split = units <= 1024 && p.kb <= 512;
+    // Few work items (a quarter of the GPU's 2048 wave slots or less): a workgroup per work item, four
+    // waves sharing its tiles; measured faster up to 512 work items, level from there to 1024.
+    const bool split = units <= 512 && p.kb <= 512;
     const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
     dim3 grid((unsigned)(split ? units : (units + 3) / 4));
     const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
