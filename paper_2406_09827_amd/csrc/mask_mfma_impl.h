@@ -125,8 +125,10 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             const int i = mt * 32 + col;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (i < n_eff) v = *(const uint4 *)(Qb + (int64_t)(i << qs) * p.qs_r + kk * 16 + hh * 8);
+                // operand rows past the sampled rows of the block repeat the last one: a repeated row cannot
+                // change a maximum, so tiles that need no causal masking take the short reduction whatever
+                // the number of rows
+                const uint4 v = *(const uint4 *)(Qb + (int64_t)(min(i, n_eff - 1) << qs) * p.qs_r + kk * 16 + hh * 8);
                 qf[mt][kk] = __builtin_bit_cast(bf16x8, v);
             }
         }
@@ -170,7 +172,6 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // and the right half of a two-block node is the node's representative.  In such a round the branch
     // table is a compact list of the blocks to score and fsl[] names the slot each one belongs to.
     bool final_mode = false;
-    const bool full_rows = n_eff == 32 * MT;
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
     // row 0 of this sequence / kv head (contiguous layout only)
     // The slice address is the same in every lane; saying so (readfirstlane) lets the loads take it as a
@@ -259,7 +260,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         // max over the admissible query rows of this lane's key column
         const int lo = t - pos0;  // block rows below lo would look into the future
         float v = -INFINITY;
-        if (full_rows && __ballot(lo > 0) == 0) {
+        if (__ballot(lo > 0) == 0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 float w[4];
