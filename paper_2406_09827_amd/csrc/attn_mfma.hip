@@ -64,17 +64,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int64_t groups = (int64_t)p.batch * p.hkv;
     const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
     int64_t group, o;
-    if (xcd_map) {  // blockIdx.x % 8 = XCD: all work of a KV head goes to one XCD's L2
-        const int64_t bid = blockIdx.x;
-        const int64_t seq = SPLIT ? (bid >> 3) : (bid >> 3) * 4 + wave;
-        group = (bid & 7) + 8 * (seq / per_group);
-        o = seq % per_group;
-    } else {
-        const int64_t lin = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
-        group = lin / per_group;
-        o = lin % per_group;
-    }
-    if (group >= groups) return;
+    if (!place_item(xcd_map, blockIdx.x, SPLIT ? 1 : 4, SPLIT ? 0 : wave, per_group, groups, group, o)) return;
     const int qb = p.nqb - 1 - (int)(o / (p.g * mtn));
     const int rem = (int)(o % (p.g * mtn));
     const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
@@ -424,8 +414,9 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     if (waves == 0) return hipSuccess;
     // few work items (a quarter of the GPU's wave slots or less): a workgroup per work item, four waves share its key tiles
     const bool split = waves <= 512;
-    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
-    dim3 grid((unsigned)(split ? waves : (waves + 3) / 4)), block(kThreads);
+    // groups worked on at a time: as many as keep their key and value rows inside the memory-side cache
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 4) : 0;
+    dim3 grid((unsigned)placed_workgroups(xcd_map, split ? 1 : 4, per_group, groups)), block(kThreads);
     const int mode = p.page_table ? 1 : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 32) ? 0 : 2);
 #define HIPATTN_LAUNCH(DV, SP)                                                                                  \
     do {                                                                                                        \

@@ -164,6 +164,47 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Placement of work items on the 8 XCDs (workgroup `bid` runs on XCD bid % 8, each XCD has its own L2).
+// A "group" is one (sequence, kv head): everything that reads the same K/V rows.  xcd_map = 0: linear
+// order.  Otherwise gc = xcd_map in {1, 2, 4, 8} groups are worked on at a time: the XCDs x with equal
+// x % gc share a group (8 / gc of them, each taking every (8/gc)-th workgroup of it) and the groups are
+// gone through gc at a time - few enough that the rows being read fit the memory-side cache.
+// upw = work items per workgroup, unit = this wave's item inside the workgroup.  False: nothing to do.
+__device__ __forceinline__ bool place_item(int xcd_map, int64_t bid, int upw, int unit, int64_t per_group, int64_t groups,
+                                           int64_t &group, int64_t &o)
+{
+    if (!xcd_map) {
+        const int64_t lin = bid * upw + unit;
+        group = lin / per_group;
+        o = lin % per_group;
+        return group < groups;
+    }
+    const int gc = xcd_map, s = 8 / gc, x = (int)(bid & 7);
+    const int64_t q = bid >> 3;
+    const int64_t wpg = per_group / upw;       // workgroups per group
+    const int64_t wpp = (wpg + s - 1) / s;     // per XCD and group
+    const int64_t w_g = (q % wpp) * s + x / gc;
+    group = (q / wpp) * gc + x % gc;
+    o = w_g * upw + unit;
+    return group < groups && w_g < wpg;
+}
+
+// Host side: the launch size that goes with place_item, and how many groups to work on at a time so that
+// gc * bytes_per_group stays below what the 256 MB memory-side cache holds comfortably.
+inline int64_t placed_workgroups(int xcd_map, int upw, int64_t per_group, int64_t groups)
+{
+    if (!xcd_map) return (groups * per_group + upw - 1) / upw;
+    const int gc = xcd_map, s = 8 / gc;
+    const int64_t wpg = per_group / upw, wpp = (wpg + s - 1) / s;
+    return 8 * (groups / gc) * wpp;
+}
+inline int groups_at_a_time(int64_t bytes_per_group)
+{
+    int gc = 8;
+    while (gc > 1 && gc * bytes_per_group > (160LL << 20)) gc >>= 1;
+    return gc;
+}
+
 template <int CTRL> __device__ __forceinline__ float dpp_f(float v)
 {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));

@@ -82,17 +82,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     const int64_t groups = (int64_t)p.batch * p.hkv;
     const int64_t per_group = (int64_t)p.g * p.nqb;
     int64_t group, o;
-    if (xcd_map) {
-        const int64_t bid = blockIdx.x;
-        const int64_t seq = SPLIT ? (bid >> 3) : (bid >> 3) * 4 + wave;
-        group = (bid & 7) + 8 * (seq / per_group);
-        o = seq % per_group;
-    } else {
-        const int64_t lin = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
-        group = lin / per_group;
-        o = lin % per_group;
-    }
-    if (group >= groups) return;
+    if (!place_item(xcd_map, blockIdx.x, SPLIT ? 1 : 4, SPLIT ? 0 : wave, per_group, groups, group, o)) return;
     const int qb = p.nqb - 1 - (int)(o / p.g);
     const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
     const int h = hk * p.g + (int)(o % p.g);
@@ -509,8 +499,9 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     // Few work items (a quarter of the GPU's 2048 wave slots or less): a workgroup per work item, four
     // waves sharing its tiles; measured faster up to 512 work items, level from there to 1024.
     const bool split = units <= 512 && p.kb <= 512;
-    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? 1 : 0;
-    dim3 grid((unsigned)(split ? units : (units + 3) / 4));
+    // groups worked on at a time: as many as keep the key rows in flight inside the memory-side cache
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 2) : 0;
+    dim3 grid((unsigned)placed_workgroups(xcd_map, split ? 1 : 4, per_group, groups));
     const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
     if constexpr (LB <= 2) {  // (with 64 channels a lane loads 4 rows of a tile, fewer than an 8-row block)
         if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, split, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, split, st);
