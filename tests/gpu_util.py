@@ -13,6 +13,9 @@ import paper_2406_09827_amd as hipattn
 from paper_2406_09827_amd import synth
 
 
+UNWRITTEN = -7   # pre-fill of the index array (no valid entry is negative)
+
+
 def oracle_problem(w, x, n_threads=8, n_sink=0, n_window=0, b_sq=1, b_sk=1, rep_pos=0, top_r=0):
     lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
     table = x["page_table"].cpu().numpy() if x["page_table"] is not None else None
@@ -32,16 +35,25 @@ def _max_len(w, x):
 
 def gpu_mask(w, x, flags=0, b_sq=1, b_sk=1, rep_pos=0, top_r=0):
     hipattn.poison_lds(0xAAAAAAAA)   # a kernel reading LDS it never wrote now sees a fixed, hostile value
+    # the index array starts out as UNWRITTEN everywhere: a work item the launch skips shows up in every_unit_written
+    idx = torch.full((w.batch, w.n_q_heads, w.n_query_blocks, w.kb), UNWRITTEN, dtype=torch.int32, device="cuda")
     return hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                      page_table=x["page_table"], max_kv_len=_max_len(w, x), flags=flags,
-                                     b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r)
+                                     b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r, indices=idx)
 
 
 def gpu_attn(w, x, idx, flags=0, sm_scale=0.0, n_sink=0, n_window=0):
     hipattn.poison_lds(0x7FC0FFEE)
+    out = torch.full_like(x["Q"], float("nan"))   # every row must be written (rows without keys are written as zeros)
     return hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                    page_table=x["page_table"], max_kv_len=_max_len(w, x), sm_scale=sm_scale, flags=flags,
-                                   n_sink=n_sink, n_window=n_window)
+                                   n_sink=n_sink, n_window=n_window, out=out)
+
+
+def every_unit_written(idx, out):
+    """No work item was skipped: nothing of the pre-filled index array and no NaN of the pre-filled output is left."""
+    assert not bool((idx == UNWRITTEN).any()), "index rows left unwritten"
+    assert not bool(torch.isnan(out.float()).any()), "output rows left unwritten"
 
 
 def check_output(got, ref, dtype):
@@ -69,6 +81,7 @@ def run_case(w, flags=0, exact=None, units=None, sm_scale=0.0, n_sink=0, n_windo
     idx_gpu = gpu_mask(w, x, flags, b_sq, b_sk, rep_pos, top_r)
     out_gpu = gpu_attn(w, x, idx_gpu, flags, sm_scale, n_sink, n_window)
     torch.cuda.synchronize()
+    every_unit_written(idx_gpu, out_gpu)
     p = oracle_problem(w, x, n_sink=n_sink, n_window=n_window, b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, top_r=top_r)
     hx = host(x)
     all_u = oracle.all_units(p)

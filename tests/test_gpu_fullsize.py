@@ -51,6 +51,7 @@ def _fullsize(w, n_units, seed):
     idx = U.gpu_mask(w, x)
     out = U.gpu_attn(w, x, idx)
     torch.cuda.synchronize()
+    U.every_unit_written(idx, out)
     _whole_result_invariants(w, x, idx)
     assert bool(torch.isfinite(out.float()).all())
     units = np.array(_sampled_units(w, n_units, seed), dtype=np.int32)
@@ -106,6 +107,15 @@ def test_c5_ragged_paged_quarter_batch():
     w = synth.scaled(synth.C5, batch=64)
     agr, err = _fullsize(w, 24, seed=5)
     print(f"C5/4: agreement {agr:.6f}, max |dO| {err:.3e}")
+
+
+def test_c2_shape_at_128k_and_256k():
+    # all eight KV heads at 128k / 256k tokens: the launches work on 4, 2 or 1 (sequence, kv head) groups at a
+    # time (placement by cache capacity), with integer-valued inputs so that the indices are exact
+    for T, n in ((131072, 16), (262144, 10)):
+        w = synth.scaled(synth.C2_INT, q_len=T, kv_len=T)
+        agr, err = _fullsize(w, n, seed=8)
+        print(f"C2@{T}: agreement {agr:.6f}, max |dO| {err:.3e}")
 
 
 def test_c4_shape_at_128k():
