@@ -231,8 +231,15 @@ def test_p2_top_r_channels(integer):
 
 
 # ----------------------------------------------------------------------------- P3
+def _read_paper_visualisation():
+    for line in open(os.path.join(GOLDEN, "paper_mask_visualisation.txt")):
+        if line.strip() and not line.startswith("#"):
+            return {k: int(v) for k, v in (item.split("=") for item in line.strip().split(";"))}
+
+
 def test_p3_paper_visualisation_structure():
-    T, k, bq, bk, d = 4096, 512, 32, 2, 8
+    g = _read_paper_visualisation()
+    T, k, bq, bk, d = g["T"], g["k"], g["bq"], g["bk"], 8
     rng = np.random.default_rng(3)
     p = Problem(1, 1, 1, d, T, T, k, bq, bk)
     Q, K = _rand((1, 1, T, d), rng), _rand((1, 1, T, d), rng)
@@ -240,9 +247,9 @@ def test_p3_paper_visualisation_structure():
     units = np.array([[0, 0, last], [0, 0, last // 2], [0, 0, 7]], dtype=np.int32)
     idx, st = oracle.mask_estimate_units(p, Q, K, units, with_stats=True)
     # last query block sees all 2048 key blocks: 2048 / 256 = groups of 8, refined in 3 iterations
-    assert st[0]["first_chunk_max"] == 8
-    assert st[0]["rounds"] == 3
-    assert st[0]["reps_scored"] == 3 * 2 * p.kb
+    assert st[0]["first_chunk_max"] == g["first_group_blocks"]
+    assert st[0]["rounds"] == g["iterations"]
+    assert st[0]["reps_scored"] == g["iterations"] * 2 * p.kb
     # key blocks touched stay within (k/bk) per branch side times log2 T iterations
     for s in st:
         assert s["reps_scored"] <= 2 * p.kb * math.ceil(math.log2(T))
