@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--q-len", type=int, default=0,
                     help="query rows per sequence, placed at the end of the context (chunked prefill, speculative decoding)")
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (a multiple of its bk)")
+    ap.add_argument("--page-size", type=int, default=-1,
+                    help="override the KV layout: tokens per page of a paged pool (a multiple of bk), 0 = contiguous")
     ap.add_argument("--bk", type=int, default=0, help="override the workload's key block size")
     ap.add_argument("--bq", type=int, default=0, help="override the workload's query block size")
     ap.add_argument("--peaks", action="store_true",
@@ -225,6 +227,8 @@ def main():
                          name=f"{w.name}_T{args.seq_len}")
     if args.q_len > 0:
         w = synth.scaled(w, q_len=args.q_len, name=f"{w.name}_q{args.q_len}")
+    if args.page_size >= 0:
+        w = synth.scaled(w, page_size=args.page_size, name=f"{w.name}_page{args.page_size}")
     if args.k > 0:
         w = synth.scaled(w, k=args.k, name=f"{w.name}_k{args.k}")
     if args.bk > 0:
@@ -292,7 +296,7 @@ def main():
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
     attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
-    plain = args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0
+    plain = args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 and args.page_size < 0
     tag = args.workload if plain and args.seq_len == 0 else "none"
     if plain and args.workload == "c2" and args.seq_len == 131072:
         tag = "c2_128k"   # the 128k prefill has counter summaries of its own   # counter summaries exist for the named workloads only
