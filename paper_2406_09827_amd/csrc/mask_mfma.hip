@@ -15,8 +15,12 @@ bool mask_mfma_supported(const KParams &p, bool bf16)
     // bf16 prefill with 1, 2, 4 (or, at head dim 128, 8) scored key rows per block (bk / b_sk) and k/bk <= 1024; everything else goes to
     // the generic kernel.  The contiguous variant addresses key rows by 32-bit byte offsets from
     // the start of a (sequence, kv head) slice, formed with a 24-bit multiply (row number x row pitch).
-    const bool fits32 = p.page_table || ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31) && p.max_kv_len < (1 << 24) &&
-                                         p.ks_r * 2 < (1 << 24));
+    // The paged variant adds a 32-bit offset inside the page to a 64-bit page base; page sizes that are
+    // not a power of two go to the generic kernel.
+    const bool fits32 = p.page_table ? (p.page_shift >= 0 && p.ks_b * 2 < (1LL << 32) && p.page_size < (1 << 24) && p.ks_r * 2 < (1 << 24) &&
+                                        (int64_t)p.page_size * p.ks_r * 2 < (1LL << 31))
+                                     : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 31) && p.max_kv_len < (1 << 24) &&
+                                        p.ks_r * 2 < (1 << 24));
     const auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
     const int rows = p.bk / p.b_sk;  // key rows scored per block
     // 1024 branch slots with one query tile: list rounds pack (slot, block index) into one word, 21 bits of index

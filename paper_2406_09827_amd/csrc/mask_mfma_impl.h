@@ -70,6 +70,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // compute unit.
     constexpr bool PACK = E == 16 && MT == 1;
     __shared__ int fsl_s[PACK ? 1 : NC][PACK ? 1 : NB / 2];
+    // With a page table: the page of every branch slot's block, looked up when the branch table is written
+    // (once per round) so that the tile loop has no dependent look-up.  With 2048 slots the table does not
+    // fit; the look-up is then issued from the tile loop, a few tiles ahead of the row loads.
+    constexpr bool PGL = PAGED && E <= 16;
+    __shared__ __attribute__((aligned(16))) int bpg_s[PGL ? NC : 1][PGL ? NB : 1];
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -125,7 +130,15 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     }
 
     uint32_t *keys = keys_s[own];
-    int *ns = nds[own], *ne = nde[own], *brt = brt_s[own], *fsl = fsl_s[PACK ? 0 : own];
+    int *ns = nds[own], *ne = nde[own], *brt = brt_s[own], *fsl = fsl_s[PACK ? 0 : own], *bpg = bpg_s[PGL ? own : 0];
+    // (page sizes are powers of two here: no branch or division in the tile loop)
+    const int *ptab = PAGED ? p.page_table + (int64_t)b * p.max_pages : nullptr;
+    const int pg0 = PGL ? ptab[0] : 0;  // empty entries load key 0
+    // branch-table entry i: first key `t0` of the block to score (-1: none); `word` is what the table holds
+    auto set_branch = [&](int i, int word, int t0) __attribute__((always_inline)) {
+        brt[i] = word;
+        if (PGL) bpg[i] = t0 >= 0 ? ptab[t0 >> p.page_shift] : pg0;
+    };
     // the waves of a work item meet here (SPLIT); otherwise the point only orders one wave's LDS traffic
     auto sync_unit = [&]() __attribute__((always_inline)) {
         if (SPLIT) __syncthreads(); else wave_lds_sync();
@@ -137,10 +150,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // scoring loop only looks the representative up.
     auto put_branches = [&](int j, int s, int e) __attribute__((always_inline)) {
         const int mid = s + ((e - s) >> 1);
-        brt[2 * j] = mid > s ? rep_block(s, mid, p.rep_pos) << lbk : -1;
-        brt[2 * j + 1] = rep_block(mid, e, p.rep_pos) << lbk;
+        const int l = mid > s ? rep_block(s, mid, p.rep_pos) << lbk : -1, r = rep_block(mid, e, p.rep_pos) << lbk;
+        set_branch(2 * j, l, l);
+        set_branch(2 * j + 1, r, r);
     };
-    for (int i = lane; i < NB; i += 64) { keys[i] = 0; brt[i] = -1; }
+    for (int i = lane; i < NB; i += 64) { keys[i] = 0; set_branch(i, -1, -1); }
     sync_unit();
     {
         const int a = Tb / kb, r = Tb % kb;
@@ -152,7 +166,6 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     }
     sync_unit();
 
-    const bf16_t *Kbase = (const bf16_t *)p.K;
     int n_tiles = (2 * kb * BK + 31) >> 5;   // every slot a tile touches is < NB
     // Rounds that run from a compact list.  A child that has its parent's representative block has the
     // parent's score, which is carried over from the round that kept the parent, and only the other
@@ -172,10 +185,16 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                             (uint32_t)__builtin_amdgcn_readfirstlane((int)slice);
     const char *Kseq = (const char *)p.K + slice_u;
     const uint32_t row_bytes = (uint32_t)p.ks_r * 2u, lc_bytes = (uint32_t)lc * 16u;
+    // paged layout: this kv head's rows of page 0, and the pitch of a page
+    const int64_t head_off = (int64_t)hk * p.ks_h * 2;
+    const char *Kpool = (const char *)p.K + (((int64_t)__builtin_amdgcn_readfirstlane((int)(head_off >> 32)) << 32) |
+                                             (uint32_t)__builtin_amdgcn_readfirstlane((int)head_off));
+    const uint32_t page_bytes = (uint32_t)p.ks_b * 2u;
 
     // Branch-table entries one tile needs: m[0..SPL-1] for the rows this lane LOADS, m[SPL] for
     // the row it SCORES (row col of the tile).
-    struct meta_t { int m[SPL + 1]; int sl; };
+    // With a page table, pg[] holds the pages of the blocks this lane loads.
+    struct meta_t { int m[SPL + 1]; int sl; int pg[PAGED ? SPL : 1]; };
     auto read_meta = [&](int tile, meta_t &mt_) __attribute__((always_inline)) {
         const int *src = brt + tile * (32 >> LB) + lg * SPL;
         if (SPL == 1) mt_.m[0] = src[0];
@@ -198,6 +217,21 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         } else {
             mt_.sl = final_mode ? fsl[min(ti, NB / 2 - 1)] : ti;  // (entries past the list are never used)
         }
+        if (PGL) {
+            const int *pgs = bpg + tile * (32 >> LB) + lg * SPL;
+            if (SPL == 1) mt_.pg[0] = pgs[0];
+            else if (SPL == 2) { const int2 v = *(const int2 *)pgs; mt_.pg[0] = v.x; mt_.pg[1] = v.y; }
+            else {
+#pragma unroll
+                for (int i = 0; i < SPL; i += 4) {
+                    const int4 v = *(const int4 *)(pgs + i);
+                    mt_.pg[i] = v.x; mt_.pg[i + 1] = v.y; mt_.pg[i + 2] = v.z; mt_.pg[i + 3] = v.w;
+                }
+            }
+        } else if (PAGED) {
+#pragma unroll
+            for (int i = 0; i < SPL; ++i) mt_.pg[i] = ptab[max(mt_.m[i], 0) >> p.page_shift];
+        }
     };
 
     // Row info of a tile from the metadata read earlier: t = key position of this lane's scored row,
@@ -219,8 +253,12 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         uint4 x;
         if (PAGED) {
             // a block never straddles a page
-            const int64_t eo = row_offset_in<true>(p, b, hk, tf, page_of_row<true>(p, b, tf)) + lc * 8;
-            x = *(const uint4 *)(Kbase + eo + (int64_t)(min(tf + (n << ks), last) - tf) * p.ks_r);
+            // a block never straddles a page: page base (one 64-bit multiply-add per block) plus a
+            // 32-bit offset inside the page
+            const int in_page = tf & (p.page_size - 1);
+            const uint32_t r = (uint32_t)(in_page + min(tf + (n << ks), last) - tf);
+            const char *pb = Kpool + (uint64_t)(uint32_t)mt_.pg[i] * page_bytes;
+            x = *(const uint4 *)(pb + (__umul24(r, row_bytes) + lc_bytes));
         } else {
             x = *(const uint4 *)(Kseq + (__umul24((uint32_t)min(tf + (n << ks), last), row_bytes) + lc_bytes));
         }
@@ -378,7 +416,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         const bool first_rule = p.rep_pos == 1;
         if (next_is_final) {
             // the branch table becomes the compact list of blocks still to be scored
-            for (int i = lane; i < 2 * kb; i += 64) brt[i] = -1;
+            for (int i = lane; i < 2 * kb; i += 64) set_branch(i, -1, -1);
         }
         sync_unit();
         if (!next_is_final) {
@@ -411,8 +449,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     if (two) {
                         const int ti = n_todo + lane_prefix_count(b2);
                         const int blk = first_rule ? mid : mid - 1;
-                        if (PACK) brt[ti] = ((carried ^ 1) << 21) | blk;
-                        else { brt[ti] = blk << lbk; fsl[ti] = carried ^ 1; }
+                        if (PACK) set_branch(ti, ((carried ^ 1) << 21) | blk, blk << lbk);
+                        else { set_branch(ti, blk << lbk, blk << lbk); fsl[ti] = carried ^ 1; }
                     }
                 }
                 n_todo += __popcll(b2);

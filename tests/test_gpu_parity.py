@@ -455,6 +455,29 @@ def test_k_over_bk_up_to_1024(integer):
 
 
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_paged_prefill_variants(integer):
+    # prefill over a paged pool on every tuned mask kernel: k/bk = 256 (page ids kept per branch slot), 512 with 32-row
+    # (packed list rounds) and 64-row query blocks, 1024 (page look-ups issued from the tile loop), list rounds with the
+    # first / last representative, a chunk of rows at the end of a long context (one work item per workgroup), and a
+    # page size that is not a power of two (generic kernel)
+    w = synth.Workload("paged_pf", 2, 4, 2, 128, 9000 + 30, 9000 + 30, 512, 32, 2, "bf16", rho=0.95, spike_every=2048,
+                       page_size=64, integer=integer, seed=111)
+    nqb = w.n_query_blocks
+    units = [(b, h, qb) for b in range(2) for h in range(4) for qb in (0, 15, 16, 17, 70, nqb // 2, nqb - 2, nqb - 1)]
+    for rep_pos in (0, 1, 2):
+        U.run_case(w, 0, units=units, rep_pos=rep_pos)
+    U.run_case(synth.scaled(w, k=1024, page_size=16), 0, units=units, n_sink=4, n_window=33)
+    U.run_case(synth.scaled(w, k=1024, bq=64, page_size=256), 0, units=[u for u in units if u[2] < nqb // 2], b_sq=2)
+    U.run_case(synth.scaled(w, k=2048, page_size=128), 0, units=units, rep_pos=2)
+    U.run_case(synth.scaled(w, k=2048, head_dim=64, bk=4, page_size=32), 0, units=units, b_sk=2)
+    U.run_case(synth.scaled(w, q_len=64, page_size=8), 0)
+    U.run_case(synth.scaled(w, q_len=64, k=1024, page_size=8), 0, rep_pos=2)
+    U.run_case(synth.scaled(w, q_len=96, k=1024, bq=64, page_size=8, head_dim=64), 0, rep_pos=1)
+    U.run_case(synth.scaled(w, page_size=48), 0, units=units)
+    U.run_case(synth.scaled(w, page_size=6, batch=1), 0, units=[u for u in units if u[0] == 0], rep_pos=2)
+
+
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_blocks_of_8_and_16_keys(integer):
     # bk = 8 (8 scored rows per block) and bk = 16 with b_sk = 2 on the tuned kernels: prefill at head dim 128,
     # decode (mask with 8 rows per block; attention walks the blocks as pieces of 4 rows)
