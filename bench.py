@@ -203,6 +203,11 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (a multiple of its bk)")
     ap.add_argument("--page-size", type=int, default=-1,
                     help="override the KV layout: tokens per page of a paged pool (a multiple of bk), 0 = contiguous")
+    ap.add_argument("--resident-frac", type=float, default=-1.0,
+                    help="token bank (paged workloads): house this fraction of the pages in a bank of resident pages and "
+                         "read the others through negative page-table entries from a backing pool; both calls also "
+                         "write their map of pages read (default: off)")
+    ap.add_argument("--host-backing", action="store_true", help="with --resident-frac: the backing pool lives in pinned host memory")
     ap.add_argument("--bk", type=int, default=0, help="override the workload's key block size")
     ap.add_argument("--bq", type=int, default=0, help="override the workload's query block size")
     ap.add_argument("--peaks", action="store_true",
@@ -242,6 +247,16 @@ def main():
     print(f"[bench] {w.name}: inputs ready in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
     kv_lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
     max_len = None if x["page_table"] is not None else w.kv_len
+    x_plain = x   # what the CPU baseline reads
+    bank = {}
+    if args.resident_frac >= 0:
+        if not w.page_size:
+            sys.exit("--resident-frac needs a paged workload (c5, or --page-size N)")
+        x = synth.token_bank(x, w, args.resident_frac, host_backing=args.host_backing, poison=0.0)
+        bank = {"k_backing": x["k_backing"], "touched": torch.zeros_like(x["page_table"], dtype=torch.uint8)}
+        bank_attn = {"k_backing": x["k_backing"], "v_backing": x["v_backing"],
+                     "touched": torch.zeros_like(x["page_table"], dtype=torch.uint8)}
+        w = synth.scaled(w, name=f"{w.name}_bank{args.resident_frac:g}{'_host' if args.host_backing else ''}")
     idx = torch.empty((w.batch, w.n_q_heads, w.n_query_blocks, w.kb), dtype=torch.int32, device="cuda")
     out = torch.empty_like(x["Q"])
 
@@ -250,14 +265,20 @@ def main():
 
     refresh = max(1, args.refresh_period) if w.q_len < w.kv_len else 1
 
-    def step(i=0):
-        if i % refresh == 0:
-            hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                      max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                      rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws)
+    def run_mask():
+        hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
+                                  max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
+                                  rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws, **bank)
+
+    def run_attn():
         hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
-                                n_sink=args.n_sink, n_window=args.n_window)
+                                n_sink=args.n_sink, n_window=args.n_window, **(bank_attn if bank else {}))
+
+    def step(i=0):
+        if i % refresh == 0:
+            run_mask()
+        run_attn()
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -276,13 +297,9 @@ def main():
     for i in range(args.steps):
         ev[i][0].record()
         if i % refresh == 0:
-            hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
-                                      max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
-                                      rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws)
+            run_mask()
         ev[i][1].record()
-        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
-                                page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
-                                n_sink=args.n_sink, n_window=args.n_window)
+        run_attn()
         ev[i][2].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -296,7 +313,7 @@ def main():
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
     attn_gbs = attn_bytes / (ms_attn * 1e-3) / 1e9
-    plain = args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 and args.page_size < 0
+    plain = args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 and args.page_size < 0 and not bank
     tag = args.workload if plain and args.seq_len == 0 else "none"
     if plain and args.workload == "c2" and args.seq_len == 131072:
         tag = "c2_128k"   # the 128k prefill has counter summaries of its own   # counter summaries exist for the named workloads only
@@ -338,12 +355,22 @@ def main():
                         "gathered_GB": attn_bytes / 1e9, "GB/s": attn_gbs},
         "roofline": roof,
     }
+    if bank:
+        # what the maps of pages read say: share of the sequences' pages each call touched, and how many of those missed
+        table = x["page_table"]
+        stats = {}
+        for name, t in (("mask_estimate", bank["touched"]), ("sparse_attn", bank_attn["touched"])):
+            read = t.bool()
+            stats[name] = {"pages_read": int(read.sum()), "misses": int((read & (table < 0)).sum())}
+        res["token_bank"] = {"resident_frac": args.resident_frac, "backing": "host" if args.host_backing else "hbm",
+                             "pages_used": sum(-(-int(n) // w.page_size) for n in (kv_lens if kv_lens is not None else [w.kv_len] * w.batch)),
+                             **stats}
     if args.peaks:
         res["measured_peaks"] = measured_peaks()
     if args.dense_yardstick and w.q_len == w.kv_len and w.kv_len <= 131072 and not w.page_size:
         res["dense_yardstick"] = dense_yardstick(w, x)
     if args.cpu_budget > 0:
-        res["cpu_baseline"] = cpu_baseline(w, x, args.cpu_budget, n_sink=args.n_sink, n_window=args.n_window,
+        res["cpu_baseline"] = cpu_baseline(w, x_plain, args.cpu_budget, n_sink=args.n_sink, n_window=args.n_window,
                                            b_sq=args.b_sq, b_sk=args.b_sk, rep_pos=args.rep_pos, top_r=args.top_r)
     print(json.dumps(res))
 

@@ -54,7 +54,8 @@ enum {
     HIP_ATTN_EDTYPE = -5,      /* dtype not HIP_ATTN_F32 / HIP_ATTN_BF16                      */
     HIP_ATTN_ETOOLARGE = -6,   /* k/bk above HIP_ATTN_MAX_KB, or bq*head_dim above the limit  */
     HIP_ATTN_EALIGN = -7,      /* a pointer or row stride is not 16-byte aligned              */
-    HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0 */
+    HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0; a backing   */
+                               /* pool or a touched map without a page table                   */
     HIP_ATTN_EWORKSPACE = -9,  /* workspace_bytes below hip_workspace_bytes()                 */
     HIP_ATTN_ELAUNCH = -1000   /* launch failure: code is HIP_ATTN_ELAUNCH - hipError_t       */
 };
@@ -117,6 +118,22 @@ typedef struct hip_problem {
      * when hip_workspace_bytes(p) is 0 (every problem without top_r). */
     void *workspace;
     size_t workspace_bytes;
+    /* Token bank with a vector-map page table (paper Sec. 3.3, "KV Token Index Translation"): with a page
+     * table, K (and V) is the pool of GPU-resident pages (the bank) and an entry e >= 0 of the table names
+     * page e of it, as always.  An entry e < 0 is a miss: the page is read from page ~e (= -e - 1) of the
+     * backing pool k_backing / v_backing instead, any memory the GPU can read (device memory, or pinned host
+     * memory for an offloaded cache), laid out and strided exactly like K / V.  hip_mask_estimate reads
+     * k_backing only; hip_sparse_attn both.  NULL = the table holds no negative entry (a negative entry is
+     * then undefined behaviour).  Each call has its own problem description, so mask estimation and sparse
+     * attention can use different banks and tables, as the paper's two offloading contexts do. */
+    const void *k_backing, *v_backing;
+    /* Device [batch, max_pages] bytes or NULL; needs a page table.  The call stores 1 at (b, i) for every
+     * logical page i of sequence b that it reads a key of: hip_mask_estimate the pages of the representative
+     * blocks it scores (any head, any query block, any round), hip_sparse_attn the pages of the keys its
+     * rows attend to (selected blocks visible to a row of their query block, sink, window).  Other bytes are
+     * left as they are, so the caller zeroes the map and may let it accumulate over calls: it is what a
+     * cache manager needs to count hits and misses (compare with the table) and to pick the pages to load. */
+    uint8_t *touched;
 } hip_problem;
 
 /*

@@ -42,6 +42,7 @@ class _Problem(ctypes.Structure):
         ("n_threads", ctypes.c_int32), ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
         ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32),
         ("top_r", ctypes.c_int32),
+        ("k_backing", ctypes.c_void_p), ("v_backing", ctypes.c_void_p), ("touched", ctypes.c_void_p),
     ]
 
 
@@ -90,6 +91,11 @@ class Problem:
     b_sk: int = 1        # mask estimation: score every b_sk-th key of the representative block
     rep_pos: int = 0     # mask estimation: representative block of a branch: 0 centre, 1 first, 2 last
     top_r: int = 0       # mask estimation: channels of largest |q| used per query row (0 = all)
+    # token bank (Sec. 3.3): pools read for negative page-table entries (entry e names page -e-1), same layout
+    # as K / V; touched [batch, max_pages] uint8 receives 1 for every logical page a call reads
+    k_backing: Optional[np.ndarray] = None
+    v_backing: Optional[np.ndarray] = None
+    touched: Optional[np.ndarray] = None
 
     @property
     def kb(self) -> int:
@@ -116,6 +122,19 @@ class Problem:
             p.page_table = a.ctypes.data
             p.page_size = self.page_size
             p.max_pages = a.shape[1]
+        for name in ("k_backing", "v_backing"):
+            x = getattr(self, name)
+            if x is not None:
+                assert self.page_table is not None and x.dtype == np.float32 and x.flags.c_contiguous
+                assert x.ndim == 4 and x.shape[1:] == (self.n_kv_heads, self.page_size, self.head_dim), x.shape
+                assert -int(np.min(self.page_table)) - 1 < x.shape[0]
+                keep.append(x)
+                setattr(p, name, x.ctypes.data)
+        if self.touched is not None:
+            t = self.touched
+            assert self.page_table is not None and t.dtype == np.uint8 and t.flags.c_contiguous
+            assert t.shape == self.page_table.shape
+            p.touched = t.ctypes.data
         return p, keep
 
 

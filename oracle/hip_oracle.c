@@ -50,6 +50,12 @@ typedef struct {
     int32_t b_sq, b_sk;        /* <= 1: every query row / every key of the block */
     int32_t rep_pos;           /* 0 centre, 1 first block, 2 last block of the branch */
     int32_t top_r;             /* 0 or >= head_dim: all channels; else channels kept per query row */
+    /* Token bank with a vector-map page table (Sec. 3.3, "KV Token Index Translation"): a page-table entry
+     * e >= 0 names page e of the pool passed as K / V (the GPU-resident bank), an entry e < 0 a miss, whose
+     * page is read from page -e-1 of the backing pool (same layout).  touched [batch, max_pages] bytes (may be
+     * NULL) receives 1 for every logical page of which a call reads a key row (other bytes are left alone). */
+    const float *k_backing, *v_backing;
+    uint8_t *touched;
 } oracle_problem;
 
 /* Statistics of one mask-estimation unit, used by the structural pins. */
@@ -66,13 +72,18 @@ typedef struct {
     int32_t page_size;
     int64_t page_stride;    /* floats between two pool pages: n_kv_heads*page_size*d               */
     int32_t d;
+    const float *backing;   /* like base, in the backing pool (pages of negative table entries)      */
+    uint8_t *touched;       /* NULL, or this sequence's row of the map of pages read                 */
 } kv_view;
 
 static const float *kv_row(const kv_view *v, int64_t t)
 {
     if (!v->pages) return v->base + t * v->d;
     int64_t page = v->pages[t / v->page_size];
-    return v->base + page * v->page_stride + (t % v->page_size) * (int64_t)v->d;
+    if (v->touched) v->touched[t / v->page_size] = 1;
+    const float *pool = v->base;
+    if (page < 0) { pool = v->backing; page = -page - 1; } /* a miss: the page lives in the backing pool */
+    return pool + page * v->page_stride + (t % v->page_size) * (int64_t)v->d;
 }
 
 /* round(a/b) to the nearest integer, halves up, exact in integers
@@ -265,11 +276,14 @@ static void attn_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
 /* exported entry points                                                     */
 /* ------------------------------------------------------------------------ */
 
-static kv_view make_view(const oracle_problem *p, const float *X, int b, int hkv)
+static kv_view make_view(const oracle_problem *p, const float *X, const float *backing, int b, int hkv)
 {
     kv_view v;
     v.d = p->head_dim;
+    v.backing = NULL; v.touched = NULL;
     if (p->page_table) {
+        if (backing) v.backing = backing + (int64_t)hkv * p->page_size * p->head_dim;
+        if (p->touched) v.touched = p->touched + (int64_t)b * p->max_pages;
         v.pages = p->page_table + (int64_t)b * p->max_pages;
         v.page_size = p->page_size;
         v.page_stride = (int64_t)p->n_kv_heads * p->page_size * p->head_dim;
@@ -317,7 +331,7 @@ int oracle_hip_mask_estimate_units(const oracle_problem *p, const float *Q, cons
         int row0 = qb * p->bq;
         int n_rows = p->q_len - row0 < p->bq ? p->q_len - row0 : p->bq;
         int64_t pos0 = kv_len - p->q_len + row0;
-        kv_view kv = make_view(p, K, b, h / g);
+        kv_view kv = make_view(p, K, p->k_backing, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
         mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, p->top_r, out + u * kb,
                   stats ? stats + u : NULL);
@@ -345,7 +359,7 @@ int oracle_hip_sparse_attn_units(const oracle_problem *p, const float *Q, const 
         int row0 = qb * p->bq;
         int n_rows = p->q_len - row0 < p->bq ? p->q_len - row0 : p->bq;
         int64_t pos0 = kv_len - p->q_len + row0;
-        kv_view kk = make_view(p, K, b, h / g), vv = make_view(p, V, b, h / g);
+        kv_view kk = make_view(p, K, p->k_backing, b, h / g), vv = make_view(p, V, p->v_backing, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
         attn_unit(q, n_rows, pos0, &kk, &vv, kv_len, idx + u * kb, kb, p->bk, sm_scale,
                   p->n_sink > 0 ? p->n_sink : 0, p->n_window > 0 ? p->n_window : 0,

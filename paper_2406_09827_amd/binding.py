@@ -35,6 +35,7 @@ class HipProblem(ctypes.Structure):
         ("n_sink", ctypes.c_int32), ("n_window", ctypes.c_int32),
         ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32), ("top_r", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("k_backing", ctypes.c_void_p), ("v_backing", ctypes.c_void_p), ("touched", ctypes.c_void_p),
     ]
 
 
@@ -118,6 +119,20 @@ def make_problem(Q: torch.Tensor, K: torch.Tensor, k: int, bq: int, bk: int,
     return p
 
 
+def _token_bank(p: HipProblem, K, page_table, k_backing, v_backing, touched) -> None:
+    """Backing pools for negative page-table entries and the map of pages read (see include/hipattn.h)."""
+    for name, x in (("k_backing", k_backing), ("v_backing", v_backing)):
+        if x is not None:
+            # device memory or pinned host memory; same layout, strides and dtype as the bank
+            assert page_table is not None and x.dim() == 4 and x.shape[1:] == K.shape[1:] and x.stride() == K.stride()
+            assert x.dtype == K.dtype and (x.is_cuda or x.is_pinned())
+            setattr(p, name, x.data_ptr())
+    if touched is not None:
+        assert page_table is not None and touched.is_cuda and touched.dtype == torch.uint8
+        assert touched.is_contiguous() and touched.shape == page_table.shape
+        p.touched = touched.data_ptr()
+
+
 def _stream(t: torch.Tensor) -> int:
     return torch.cuda.current_stream(t.device).cuda_stream
 
@@ -166,12 +181,14 @@ def probe_mfma(out: torch.Tensor, workgroups: int, iters: int) -> float:
 
 def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,
                       flags: int = 0, indices: Optional[torch.Tensor] = None, b_sq: int = 1, b_sk: int = 1,
-                      rep_pos: int = 0, top_r: int = 0, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      rep_pos: int = 0, top_r: int = 0, workspace: Optional[torch.Tensor] = None,
+                      k_backing: Optional[torch.Tensor] = None, touched: Optional[torch.Tensor] = None) -> torch.Tensor:
     """int32 indices [B, Hq, ceil(Tq/bq), k/bk] of the selected key blocks (see include/hipattn.h)."""
     _need_gpu(Q, K, kv_lens, page_table, indices)
     lib = load()
     p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
     p.b_sq, p.b_sk, p.rep_pos, p.top_r = b_sq, b_sk, rep_pos, top_r
+    _token_bank(p, K, page_table, k_backing, None, touched)
     need = lib.hip_workspace_bytes(ctypes.byref(p))
     if need:
         if workspace is None:
@@ -191,7 +208,9 @@ def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=N
 
 def hip_sparse_attn(Q, K, V, indices, k: int, bq: int, bk: int, kv_lens=None, page_table=None,
                     max_kv_len=None, sm_scale: float = 0.0, flags: int = 0,
-                    out: Optional[torch.Tensor] = None, n_sink: int = 0, n_window: int = 0) -> torch.Tensor:
+                    out: Optional[torch.Tensor] = None, n_sink: int = 0, n_window: int = 0,
+                    k_backing: Optional[torch.Tensor] = None, v_backing: Optional[torch.Tensor] = None,
+                    touched: Optional[torch.Tensor] = None) -> torch.Tensor:
     """O [B, Hq, Tq, d]: attention of every query row over its block's selected keys (plus the first
     n_sink and the n_window most recent keys)."""
     _need_gpu(Q, K, V, indices, kv_lens, page_table, out)
@@ -203,6 +222,7 @@ def hip_sparse_attn(Q, K, V, indices, k: int, bq: int, bk: int, kv_lens=None, pa
     assert indices.dtype == torch.int32 and indices.is_contiguous()
     p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, sm_scale, flags, O=out)
     p.n_sink, p.n_window = n_sink, n_window
+    _token_bank(p, K, page_table, k_backing, v_backing, touched)
     rc = lib.hip_sparse_attn(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(), indices.data_ptr(),
                              out.data_ptr(), _stream(Q))
     if rc != 0:

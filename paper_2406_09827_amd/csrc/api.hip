@@ -27,6 +27,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     if (p.k / p.bk > HIP_ATTN_MAX_KB) return HIP_ATTN_ETOOLARGE;
     if (p.page_table && (p.page_size <= 0 || p.page_size % p.bk || p.max_pages <= 0)) return HIP_ATTN_EPAGE;
     if (p.page_table && (int64_t)p.max_pages * p.page_size < p.max_kv_len) return HIP_ATTN_EPAGE;
+    if (!p.page_table && (p.k_backing || p.v_backing || p.touched)) return HIP_ATTN_EPAGE;
 
     const int d = p.head_dim;
     const int nqb = (p.q_len + p.bq - 1) / p.bq;
@@ -38,6 +39,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     // a single query row is a one-row query block whatever bq says: the decode kernels then serve it
     if (p.q_len == 1) kp.bq = 1;
     kp.kv_lens = p.kv_lens; kp.page_table = p.page_table;
+    kp.Kback = p.k_backing; kp.Vback = p.v_backing; kp.touched = p.touched;
     kp.page_size = p.page_size; kp.max_pages = p.max_pages;
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
     kp.b_sq = (p.b_sq > 1 && p.q_len > 1) ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
@@ -87,7 +89,9 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     if (kp.batch == 0 || kp.q_len == 0) return HIP_ATTN_OK;  // no work units: nothing is read or written
     if (!Q || !K || !indices) return HIP_ATTN_ENULL;
     if (!aligned16(Q) || !aligned16(K)) return HIP_ATTN_EALIGN;
+    if (p->k_backing && !aligned16(p->k_backing)) return HIP_ATTN_EALIGN;
     kp.Q = Q; kp.K = K; kp.idx_out = indices;
+    if (!kp.Kback) kp.Kback = K;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
@@ -121,9 +125,16 @@ int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const vo
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
-    if (!generic && attn_mfma_supported(kp, bf16)) return launch_result(launch_attn_mfma(kp, st));
-    if (!generic && attn_decode_supported(kp, bf16)) return launch_result(launch_attn_decode(kp, st));
-    return launch_result(launch_attn_generic(kp, bf16, st));
+    if (p->k_backing && !aligned16(p->k_backing)) return HIP_ATTN_EALIGN;
+    if (p->v_backing && !aligned16(p->v_backing)) return HIP_ATTN_EALIGN;
+    if (!kp.Kback) kp.Kback = K;
+    if (!kp.Vback) kp.Vback = V;
+    hipError_t e;
+    if (!generic && attn_mfma_supported(kp, bf16)) e = launch_attn_mfma(kp, st);
+    else if (!generic && attn_decode_supported(kp, bf16)) e = launch_attn_decode(kp, st);
+    else e = launch_attn_generic(kp, bf16, st);
+    if (e == hipSuccess && kp.touched) e = launch_touch_attn(kp, st);  // the map of pages read, from the index array
+    return launch_result(e);
 }
 
 size_t hip_workspace_bytes(const hip_problem *p)
@@ -145,7 +156,7 @@ const char *hip_strerror(int code)
         case HIP_ATTN_EDTYPE: return "dtype must be HIP_ATTN_F32 or HIP_ATTN_BF16";
         case HIP_ATTN_ETOOLARGE: return "k/bk or the number of work units exceeds the compiled maximum";
         case HIP_ATTN_EALIGN: return "pointer or stride not 16-byte aligned";
-        case HIP_ATTN_EPAGE: return "invalid page table description";
+        case HIP_ATTN_EPAGE: return "invalid page table description (or a backing pool / touched map without a page table)";
         case HIP_ATTN_EWORKSPACE: return "workspace smaller than hip_workspace_bytes()";
         default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
     }
@@ -179,6 +190,6 @@ int hip_attn_probe_mfma(float *out, int32_t workgroups, int32_t iters, void *str
     return launch_result(launch_probe_mfma(out, workgroups, iters, static_cast<hipStream_t>(stream)));
 }
 
-int hip_attn_version(void) { return 103; }
+int hip_attn_version(void) { return 104; }
 
 }  // extern "C"

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p, int su
     constexpr int LPR = D / 8, RPW = 64 / LPR;
     constexpr int U = ROWS / BK;  // blocks per lane group and stage: ROWS key + ROWS value row loads per lane, two stages in flight
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // (uniform: what follows from it stays in scalar registers)
     const int grp = lane / LPR, lc = lane % LPR;
     const int64_t wg = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
     if (wg >= (int64_t)p.batch * p.hq) return;
@@ -84,12 +84,14 @@ __global__ __launch_bounds__(kThreads) void attn_decode_kernel(KParams p, int su
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int f = first[u];
-            const int64_t off = row_offset_in<PAGED>(p, b, hk, f >= 0 ? f : 0, pg[u]) + lc * 8;
+            const int64_t off = row_offset_in<PAGED>(p, b, hk, f >= 0 ? f : 0, page_in_pool(pg[u])) + lc * 8;
+            // (a negative page-table entry names a page of the backing pools)
+            const bf16_t *Kp = (const bf16_t *)pool_of(pg[u], Kbase, p.Kback), *Vp = (const bf16_t *)pool_of(pg[u], Vbase, p.Vback);
 #pragma unroll
             for (int n = 0; n < BK; ++n) {
                 const int dn = f >= 0 ? min(n, kv_len - 1 - f) : 0;
-                const uint4 x = *(const uint4 *)(Kbase + off + (int64_t)dn * p.ks_r);
-                const uint4 y = *(const uint4 *)(Vbase + off + (int64_t)dn * p.ks_r);
+                const uint4 x = *(const uint4 *)(Kp + off + (int64_t)dn * p.ks_r);
+                const uint4 y = *(const uint4 *)(Vp + off + (int64_t)dn * p.ks_r);
                 const int q4 = 4 * (u * BK + n);
                 kr[q4] = x.x; kr[q4 + 1] = x.y; kr[q4 + 2] = x.z; kr[q4 + 3] = x.w;
                 vr[q4] = y.x; vr[q4 + 1] = y.y; vr[q4 + 2] = y.z; vr[q4 + 3] = y.w;

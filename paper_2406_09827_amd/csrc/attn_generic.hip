@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(KParams p)
     for (int i = tid; i < n_rows * D; i += kThreads) q_s[i] = ld_f32(Qb + (int64_t)(i / D) * p.qs_r + (i % D));
     __syncthreads();
 
-    const T *Kbase = (const T *)p.K, *Vbase = (const T *)p.V;
+    const T *Kbase = (const T *)p.K, *Vbase = (const T *)p.V, *Kback = (const T *)p.Kback, *Vback = (const T *)p.Vback;
     T *Ob = (T *)p.O + (int64_t)b * p.os_b + (int64_t)h * p.os_h + (int64_t)row0 * p.os_r;
     const int n_sel = kb * bk;
 
@@ -80,10 +80,11 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(KParams p)
                 }
             }
             int64_t off = 0;
+            bool miss = false;
             float s = -INFINITY;
             if (valid) {
-                off = kv_row_offset(p, b, hk, t);
-                const T *krow = Kbase + off;
+                off = kv_row_offset(p, b, hk, t, miss);
+                const T *krow = (miss ? Kback : Kbase) + off;
                 float dot = 0.f;
                 for (int c = 0; c < D; ++c) dot = fmaf(qrow[c], ld_f32(krow + c), dot);
                 s = dot * p.sm_scale;
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(KParams p)
                 if (!((live >> src) & 1)) continue;
                 const float ps = __shfl(pr, src, 64);
                 const int64_t so = __shfl((long long)off, src, 64);
-                const T *vrow = Vbase + so;
+                const T *vrow = (__shfl((int)miss, src, 64) ? Vback : Vbase) + so;
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) acc[c] = fmaf(ps, ld_f32(vrow + lane + 64 * c), acc[c]);
             }

@@ -182,9 +182,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             int64_t eo;
+            const bf16_t *Kp = Kbase, *Vp = Vbase;
             if (PAGED) {
                 const int tr = max(tkl[j], 0);
-                eo = row_offset_in<true>(p, b, hk, tr, (int)off[j]) + lc * 8;
+                // (a negative page-table entry names a page of the backing pools)
+                eo = row_offset_in<true>(p, b, hk, tr, page_in_pool((int)off[j])) + lc * 8;
+                Kp = (const bf16_t *)pool_of((int)off[j], Kbase, p.Kback);
+                Vp = (const bf16_t *)pool_of((int)off[j], Vbase, p.Vback);
             } else {
                 eo = seq_off + ((int64_t)off[j] << 3) + lc * 8;
             }
@@ -194,8 +198,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 x = *(const uint4 *)(Kseq + vo);
                 y = *(const uint4 *)(Vseq + vo);
             } else {
-                x = *(const uint4 *)(Kbase + eo);
-                y = *(const uint4 *)(Vbase + eo);
+                x = *(const uint4 *)(Kp + eo);
+                y = *(const uint4 *)(Vp + eo);
             }
             RK[4 * j] = x.x; RK[4 * j + 1] = x.y; RK[4 * j + 2] = x.z; RK[4 * j + 3] = x.w;
             RV[4 * j] = y.x; RV[4 * j + 1] = y.y; RV[4 * j + 2] = y.z; RV[4 * j + 3] = y.w;

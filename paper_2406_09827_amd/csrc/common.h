@@ -16,6 +16,8 @@ struct KParams {
     const int32_t *idx_in;     // sparse attention input
     const int32_t *kv_lens;    // [batch] or nullptr
     const int32_t *page_table; // [batch, max_pages] or nullptr
+    const void *Kback, *Vback; // backing pools for page-table entries < 0 (entry e names page ~e), or nullptr
+    uint8_t *touched;          // [batch, max_pages] or nullptr: 1 is stored for every logical page read
     int64_t qs_b, qs_h, qs_r;  // element strides
     int64_t ks_b, ks_h, ks_r;
     int64_t os_b, os_h, os_r;
@@ -57,18 +59,37 @@ __device__ __forceinline__ uint32_t score_key(float f)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Element offset of logical key/value row t of sequence b, kv head h.
-__device__ __forceinline__ int64_t kv_row_offset(const KParams &p, int b, int h, int t)
+// Element offset of logical key/value row t of sequence b, kv head h inside its pool; `miss` says that the
+// page-table entry is negative, i.e. that the row lives in the backing pool (entry e names page ~e of it).
+__device__ __forceinline__ int64_t kv_row_offset(const KParams &p, int b, int h, int t, bool &miss)
 {
+    miss = false;
     if (p.page_table) {
         int pi, in_page;
         if (p.page_shift >= 0) { pi = t >> p.page_shift; in_page = t & (p.page_size - 1); }
         else { pi = t / p.page_size; in_page = t - pi * p.page_size; }
-        const int pg = p.page_table[(int64_t)b * p.max_pages + pi];
-        return (int64_t)pg * p.ks_b + (int64_t)h * p.ks_h + (int64_t)in_page * p.ks_r;
+        const int e = p.page_table[(int64_t)b * p.max_pages + pi];
+        miss = e < 0;
+        return (int64_t)(e < 0 ? ~e : e) * p.ks_b + (int64_t)h * p.ks_h + (int64_t)in_page * p.ks_r;
     }
     return (int64_t)b * p.ks_b + (int64_t)h * p.ks_h + (int64_t)t * p.ks_r;
 }
+// Logical page of key t.
+__device__ __forceinline__ int logical_page(const KParams &p, int t)
+{
+    return p.page_shift >= 0 ? (t >> p.page_shift) : (t / p.page_size);
+}
+// Marks the logical page of key t of sequence b as read (callers check p.touched first).
+__device__ __forceinline__ void touch_page(const KParams &p, int b, int t)
+{
+    p.touched[(int64_t)b * p.max_pages + logical_page(p, t)] = 1;
+}
+// The pool a page-table entry points into, and the page inside it.
+__device__ __forceinline__ const void *pool_of(int entry, const void *pool, const void *backing)
+{
+    return entry < 0 ? backing : pool;
+}
+__device__ __forceinline__ int page_in_pool(int entry) { return entry < 0 ? ~entry : entry; }
 
 // The same in two steps, for kernels that want all page-table reads of a batch of rows in
 // flight before the first dependent row load is issued (a dependent load in the middle of a
@@ -84,6 +105,13 @@ template <bool PAGED> __device__ __forceinline__ int64_t row_offset_in(const KPa
     if (!PAGED) return (int64_t)b * p.ks_b + (int64_t)h * p.ks_h + (int64_t)t * p.ks_r;
     const int in_page = p.page_shift >= 0 ? (t & (p.page_size - 1)) : (t % p.page_size);
     return (int64_t)page * p.ks_b + (int64_t)h * p.ks_h + (int64_t)in_page * p.ks_r;
+}
+// Element offset of row t from the start of the resident pool when the page-table entry may be negative:
+// `delta` is the distance (in elements) from the resident pool to the backing pool.
+template <bool PAGED> __device__ __forceinline__ int64_t row_offset_bank(const KParams &p, int b, int h, int t, int entry, int64_t delta)
+{
+    if (!PAGED) return row_offset_in<false>(p, b, h, t, 0);
+    return row_offset_in<true>(p, b, h, t, entry < 0 ? ~entry : entry) + (entry < 0 ? delta : 0);
 }
 
 __device__ __forceinline__ int lane_prefix_count(uint64_t mask)

@@ -19,5 +19,6 @@ constexpr int kProbeReadGrid = 256 * 32;  // workgroups of the read probe (its o
 hipError_t launch_probe_read(uint32_t *out, const void *src, int64_t bytes, hipStream_t st);
 hipError_t launch_probe_mfma(float *out, int workgroups, int iters, hipStream_t st);
 hipError_t launch_topr_mask(const KParams &p, bool bf16, void *dst, hipStream_t st);
+hipError_t launch_touch_attn(const KParams &p, hipStream_t st);
 
 }  // namespace hipattn

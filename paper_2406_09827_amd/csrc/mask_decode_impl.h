@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     __shared__ int nds[NW][2][NB / 2], nde[NW][2][NB / 2];
     __shared__ uint32_t nkey_s[CARRY ? NW : 1][2][CARRY ? NB / 2 : 1];  // score key of the branch that became each node
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // (uniform: what follows from it stays in scalar registers)
     const int grp = lane / LPR, lc = lane % LPR;
     const int own = SPLIT ? 0 : wave;  // which LDS copy
     int64_t wg;
@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     sync_problem();
 
     const bf16_t *Kbase = (const bf16_t *)p.K;
+    const int64_t back_delta = (const bf16_t *)p.Kback - Kbase;  // elements from the resident pool to the backing pool
     int cur = 0;
     bool carry = false;  // set after the first iteration, unless the centre block represents a branch
     // side of a node's children that is scored in a carry round: the left one when the LAST block
@@ -127,7 +128,8 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int t = t0[u] >= 0 ? t0[u] : 0;
-                const bf16_t *src = Kbase + row_offset_in<PAGED>(p, b, hk, t, pg[u]) + lc * 8;
+                // (a negative page-table entry names a page of the backing pool)
+                const bf16_t *src = Kbase + row_offset_bank<PAGED>(p, b, hk, t, pg[u], back_delta) + lc * 8;
 #pragma unroll
                 for (int n = 0; n < BK; ++n) {
                     // rows past the end of the sequence re-read its last row and are ignored below
@@ -179,6 +181,18 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         }
         sync_problem();
 
+        if (PAGED && p.touched) {
+            // pages read this round: the representative block of every real branch (a branch whose score was
+            // carried over had the same block read in an earlier round)
+            for (int slot = tix; slot < 2 * kb; slot += tn) {
+                if (keys[slot] != 0u) {
+                    const int node = slot >> 1;
+                    const int s = ns[node], e = ne[node];
+                    const int mid = s + ((e - s) >> 1);
+                    touch_page(p, b, rep_block((slot & 1) ? mid : s, (slot & 1) ? e : mid, p.rep_pos) * bk);
+                }
+            }
+        }
         uint32_t key[E];
         bool keep[E];
         int dest[E];

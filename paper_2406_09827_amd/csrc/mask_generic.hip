@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
     }
     __syncthreads();
 
-    const T *Kbase = (const T *)p.K;
+    const T *Kbase = (const T *)p.K, *Kback = (const T *)p.Kback;
     const int grp = tid >> 4, l16 = tid & 15;
 
     // maxlen bounds the longest node; one more round than strictly needed is a no-op
@@ -79,7 +79,10 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
             if (e <= s) continue;
             const int t = rep_block(s, e, p.rep_pos) * bk + n;  // key of the representative block
             if (t >= kv_len) continue;
-            const T *krow = Kbase + kv_row_offset(p, b, hk, t) + l16 * CH;
+            bool miss;
+            const int64_t off = kv_row_offset(p, b, hk, t, miss);
+            const T *krow = (miss ? Kback : Kbase) + off + l16 * CH;
+            if (p.touched && l16 == 0) touch_page(p, b, t);
             float kreg[CH];
 #pragma unroll
             for (int c = 0; c < CH; ++c) kreg[c] = ld_f32(krow + c);

@@ -138,6 +138,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     auto set_branch = [&](int i, int word, int t0) __attribute__((always_inline)) {
         brt[i] = word;
         if (PGL) bpg[i] = t0 >= 0 ? ptab[t0 >> p.page_shift] : pg0;
+        if (PAGED && p.touched && t0 >= 0) touch_page(p, b, t0);
     };
     // the waves of a work item meet here (SPLIT); otherwise the point only orders one wave's LDS traffic
     auto sync_unit = [&]() __attribute__((always_inline)) {
@@ -189,6 +190,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     const int64_t head_off = (int64_t)hk * p.ks_h * 2;
     const char *Kpool = (const char *)p.K + (((int64_t)__builtin_amdgcn_readfirstlane((int)(head_off >> 32)) << 32) |
                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)head_off));
+    const char *Kpool_back = (const char *)p.Kback + (Kpool - (const char *)p.K);
     const uint32_t page_bytes = (uint32_t)p.ks_b * 2u;
 
     // Branch-table entries one tile needs: m[0..SPL-1] for the rows this lane LOADS, m[SPL] for
@@ -257,7 +259,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             // 32-bit offset inside the page
             const int in_page = tf & (p.page_size - 1);
             const uint32_t r = (uint32_t)(in_page + min(tf + (n << ks), last) - tf);
-            const char *pb = Kpool + (uint64_t)(uint32_t)mt_.pg[i] * page_bytes;
+            // (a negative page-table entry names a page of the backing pool)
+            const char *pb = (mt_.pg[i] < 0 ? Kpool_back : Kpool) + (uint64_t)(uint32_t)page_in_pool(mt_.pg[i]) * page_bytes;
             x = *(const uint4 *)(pb + (__umul24(r, row_bytes) + lc_bytes));
         } else {
             x = *(const uint4 *)(Kseq + (__umul24((uint32_t)min(tf + (n << ks), last), row_bytes) + lc_bytes));

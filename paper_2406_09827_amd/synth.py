@@ -205,3 +205,46 @@ def make_inputs(w: Workload, device="cpu", threads: int = 8) -> Dict[str, object
         out["kv_lens"] = torch.from_numpy(lens).to(device)
     out.update(Q=Q, K=K, V=V)
     return out
+
+
+def token_bank(x: Dict[str, object], w: Workload, resident_frac: float, host_backing: bool = False,
+               poison: float = 7.0) -> Dict[str, object]:
+    """Re-houses a paged input as a bank of resident pages plus a backing pool (the layout of the paper's
+    KV cache offloading, Sec. 3.3): every used page is resident with probability `resident_frac`.
+
+    Returns a copy of `x` in which K, V are the bank [n_resident, Hkv, page, d] (resident pages in random order),
+    `k_backing`, `v_backing` the full pools (in pinned host memory with `host_backing`), and `page_table` holds
+    the bank slot (>= 0) of a resident page and -(backing page) - 1 of any other.  With `poison`, the backing
+    copies of the resident pages are overwritten with that value, so a look-up that goes to the wrong pool shows.
+    """
+    assert w.page_size and x["page_table"] is not None
+    K, V = x["K"], x["V"]
+    table = x["page_table"].cpu().numpy().astype(np.int64)
+    lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else np.full(w.batch, w.kv_len)
+    n_used = (lens.astype(np.int64) + w.page_size - 1) // w.page_size
+    used = np.arange(table.shape[1])[None, :] < n_used[:, None]
+    rng = _rng(w.seed, 9)
+    resident = used & (rng.random(table.shape) < resident_frac)
+    pages = table[resident]                       # backing pages that get a bank slot
+    slots = rng.permutation(pages.size)
+    new_table = np.where(used, -table - 1, 0)
+    new_table[resident] = slots
+    order = np.empty(max(pages.size, 1), dtype=np.int64)
+    order[:] = pages[0] if pages.size else 0
+    order[slots] = pages
+    sel = torch.from_numpy(order).to(K.device)
+    out = dict(x)
+    out["K"], out["V"] = K[sel].contiguous(), V[sel].contiguous()
+    kb_, vb_ = K.clone(), V.clone()
+    if poison and pages.size:
+        kb_[sel] = poison
+        vb_[sel] = poison
+    if not pages.size:
+        out["K"].fill_(poison)
+        out["V"].fill_(poison)
+    if host_backing:
+        kb_, vb_ = kb_.cpu().pin_memory(), vb_.cpu().pin_memory()
+    out["k_backing"], out["v_backing"] = kb_, vb_
+    out["page_table"] = torch.from_numpy(new_table.astype(np.int32)).to(K.device)
+    out["resident"] = resident
+    return out

@@ -130,3 +130,47 @@ def check_indices_valid(w, x, idx, units):
         assert (row[nv:] == hipattn.SENTINEL).all()
         assert (v % w.bk == 0).all() and (v >= 0).all() and (v < L).all()
         assert (np.diff(v) > 0).all()
+
+
+def run_bank_case(w, resident_frac, flags=0, host_backing=False, n_sink=0, n_window=0, b_sk=1, rep_pos=0, units=None):
+    """Token bank (paper Sec. 3.3): the workload's pages housed as bank + backing pool.  Indices and outputs must be
+    bitwise those of the plain paged call (same arithmetic, other addresses); the maps of pages read must equal the
+    oracle's (integer-valued inputs: both sides walk the same branches).  Returns the fraction of misses among the
+    pages mask estimation read."""
+    assert w.page_size and w.integer
+    x = synth.make_inputs(w, device="cuda", threads=4)
+    xb = synth.token_bank(x, w, resident_frac, host_backing=host_backing)
+    kw = dict(kv_lens=x["kv_lens"], max_kv_len=_max_len(w, x), flags=flags)
+    idx = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, page_table=x["page_table"], b_sk=b_sk, rep_pos=rep_pos, **kw)
+    out = hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, page_table=x["page_table"],
+                                  n_sink=n_sink, n_window=n_window, **kw)
+    hipattn.poison_lds(0xAAAAAAAA)
+    tm, ta = torch.zeros_like(xb["page_table"], dtype=torch.uint8), torch.zeros_like(xb["page_table"], dtype=torch.uint8)
+    idx_b = torch.full_like(idx, UNWRITTEN)
+    hipattn.hip_mask_estimate(x["Q"], xb["K"], w.k, w.bq, w.bk, page_table=xb["page_table"], b_sk=b_sk, rep_pos=rep_pos,
+                              k_backing=xb["k_backing"], touched=tm, indices=idx_b, **kw)
+    out_b = hipattn.hip_sparse_attn(x["Q"], xb["K"], xb["V"], idx_b, w.k, w.bq, w.bk, page_table=xb["page_table"],
+                                    n_sink=n_sink, n_window=n_window, k_backing=xb["k_backing"], v_backing=xb["v_backing"],
+                                    touched=ta, out=torch.full_like(x["Q"], float("nan")), **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(idx_b, idx), "indices depend on where the pages live"
+    assert torch.equal(out_b.view(torch.int16 if w.dtype == "bf16" else torch.int32),
+                       out.view(torch.int16 if w.dtype == "bf16" else torch.int32)), "outputs depend on where the pages live"
+    # the oracle on the bank layout: indices (all units, or a sample) and both maps (these need every unit)
+    lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
+    tb = xb["page_table"].cpu().numpy()
+    hx = {n: xb[n].float().cpu().numpy() for n in ("K", "V", "k_backing", "v_backing")}
+    Q = x["Q"].float().cpu().numpy()
+    om, oa = np.zeros(tb.shape, np.uint8), np.zeros(tb.shape, np.uint8)
+    mk = lambda touched: oracle.Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
+                                        kv_lens=lens, page_table=tb, page_size=w.page_size, n_threads=8, n_sink=n_sink,
+                                        n_window=n_window, b_sk=b_sk, rep_pos=rep_pos, k_backing=hx["k_backing"],
+                                        v_backing=hx["v_backing"], touched=touched)
+    idx_ref = oracle.mask_estimate(mk(om), Q, hx["K"])
+    assert np.array_equal(idx_b.cpu().numpy(), idx_ref)
+    assert np.array_equal(tm.cpu().numpy(), om), "pages read by mask estimation"
+    o_ref = oracle.sparse_attn(mk(oa), Q, hx["K"], hx["V"], idx_ref)
+    assert np.array_equal(ta.cpu().numpy(), oa), "pages read by sparse attention"
+    check_output(out_b.float().cpu().numpy(), o_ref, w.dtype)
+    read = om.astype(bool)
+    return float((tb[read] < 0).mean()) if read.any() else 0.0

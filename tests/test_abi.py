@@ -44,6 +44,10 @@ def _ok_problem():
     (lambda p: (setattr(p, "k", 4096), setattr(p, "bk", 2)), -6),
     (lambda p: (setattr(p, "page_table", 4096), setattr(p, "page_size", 3), setattr(p, "max_pages", 64)), -8),
     (lambda p: setattr(p, "q_strides", (ctypes.c_int64 * 3)(8192, 130, 2)), -7),
+    (lambda p: setattr(p, "k_backing", 4096), -8),     # a backing pool / a map of pages read needs a page table
+    (lambda p: setattr(p, "touched", 4096), -8),
+    (lambda p: (setattr(p, "page_table", 4096), setattr(p, "page_size", 4), setattr(p, "max_pages", 64),
+                setattr(p, "k_backing", 4100)), -7),
 ])
 def test_argument_errors_before_launch(mutate, code):
     lib = hipattn.load()

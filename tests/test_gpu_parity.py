@@ -477,6 +477,44 @@ def test_paged_prefill_variants(integer):
     U.run_case(synth.scaled(w, page_size=6, batch=1), 0, units=[u for u in units if u[0] == 0], rep_pos=2)
 
 
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("resident_frac", [0.0, 0.5, 1.0])
+def test_token_bank_decode(flags, resident_frac):
+    # the paper's offloading layout (Sec. 3.3): a bank of resident pages, misses read from a backing pool, the map of
+    # pages read.  Ragged paged decode on the tuned and the generic kernels; a block per page and larger pages.
+    w = synth.Workload("bank_dec", 5, 8, 2, 128, 1, 7000, 256, 1, 2, "bf16", rho=0.9, ragged=(900, 7000), page_size=16,
+                       integer=True, seed=121)
+    miss = U.run_bank_case(w, resident_frac, flags, n_sink=3, n_window=20)
+    assert abs(miss - (1.0 - resident_frac)) < 0.1
+    U.run_bank_case(synth.scaled(w, page_size=2, head_dim=64), resident_frac, flags)
+    U.run_bank_case(synth.scaled(w, bk=4, k=512, page_size=64, batch=2), resident_frac, flags, rep_pos=2, b_sk=2)
+    U.run_bank_case(synth.scaled(w, batch=300, n_q_heads=2, n_kv_heads=1, kv_len=2000, ragged=(300, 2000), k=128),
+                    resident_frac, flags)   # wave-per-problem variants
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+def test_token_bank_prefill(flags):
+    # the same over the prefill kernels: 32- and 64-row query blocks, list rounds, k/bk = 512 and 1024, a chunk of rows
+    w = synth.Workload("bank_pf", 2, 4, 2, 128, 2500 + 30, 2500 + 30, 128, 32, 2, "bf16", rho=0.95, page_size=32,
+                       integer=True, seed=122)
+    U.run_bank_case(w, 0.5, flags, n_sink=4, n_window=40)
+    U.run_bank_case(synth.scaled(w, bq=64, head_dim=64, page_size=8), 0.3, flags, rep_pos=1)
+    U.run_bank_case(synth.scaled(w, q_len=70), 0.7, flags, rep_pos=2)
+    if not flags:
+        U.run_bank_case(synth.scaled(w, k=1024, q_len=400, batch=1, kv_len=6000), 0.5)
+        U.run_bank_case(synth.scaled(w, k=2048, q_len=200, batch=1, kv_len=6000, page_size=4), 0.5)
+    U.run_bank_case(synth.scaled(w, dtype="fp32", q_len=300, head_dim=64), 0.5, flags)
+    U.run_bank_case(synth.scaled(w, page_size=6, q_len=300), 0.5, flags)   # not a power of two
+
+
+def test_token_bank_in_host_memory():
+    # the backing pool in pinned host memory (an offloaded KV cache): misses are read over the host link
+    w = synth.Workload("bank_host", 4, 8, 2, 128, 1, 5000, 256, 1, 2, "bf16", rho=0.9, ragged=(900, 5000), page_size=16,
+                       integer=True, seed=123)
+    U.run_bank_case(w, 0.8, host_backing=True, n_window=16)
+    U.run_bank_case(synth.scaled(w, q_len=64, bq=32, batch=1, ragged=None), 0.8, host_backing=True)
+
+
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_blocks_of_8_and_16_keys(integer):
     # bk = 8 (8 scored rows per block) and bk = 16 with b_sk = 2 on the tuned kernels: prefill at head dim 128,

@@ -13,6 +13,8 @@ Each test names the passage of the paper, or the mathematical fact, it checks:
   P8  on AR(1) keys HiP recalls more of the exact top-k than uniformly random blocks (Sec. 4)
   P9  sink + sliding window (appendix "Block Sparse Flash Attention"): a window covering everything is dense
       causal attention; selected blocks + sink + window == dense attention with the union as additive mask
+  P10 token bank (Sec. 3.3): results do not depend on which pages are resident; the map of pages read equals
+      the pages of the blocks the literal transcription scores / of the keys in the rows' key sets
 """
 import math
 import os
@@ -63,9 +65,10 @@ def test_p1_dense_equivalence(T, bq, bk, d, hq, hkv):
 
 
 # ----------------------------------------------------------------------------- P2
-def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0):
+def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, scored=None):
     """Scores for the literal transcription are formed here from exact rationals of the
-    (integer-valued) inputs or from float64 dot products."""
+    (integer-valued) inputs or from float64 dot products.  `scored` (a list) collects the 1-based
+    blocks whose score is asked for."""
     g = p.n_q_heads // p.n_kv_heads
     row0 = qb * p.bq
     n_rows = min(p.bq, p.q_len - row0)
@@ -78,6 +81,8 @@ def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0):
     Kd = K[b, h // g].astype(np.float64)
 
     def score(r1):
+        if scored is not None:
+            scored.append(r1)
         best = -math.inf
         for n in range(0, p.bk, b_sk):
             t = (r1 - 1) * p.bk + n
@@ -487,3 +492,95 @@ def test_p8_recall_beats_random_on_local_keys():
         rnd_hit += len(top & set(rng.choice(i + 1, size=w.k, replace=False).tolist()))
         tot += w.k
     assert hit / tot > 2.0 * rnd_hit / tot, (hit / tot, rnd_hit / tot)
+
+
+# ----------------------------------------------------------------------------- P10
+def _bank_case(resident_frac, q_len, seed):
+    w = synth.Workload("bank", 3, 4, 2, 8, q_len, 150, 12, min(q_len, 4), 2, "fp32", ragged=(60, 150), page_size=4,
+                       integer=True, seed=seed)
+    x = synth.make_inputs(w, threads=1)
+    xb = synth.token_bank(x, w, resident_frac)
+    return w, x, xb
+
+
+def _np(x, *names):
+    return [x[n].float().numpy() if x[n].is_floating_point() else x[n].numpy() for n in names]
+
+
+@pytest.mark.parametrize("resident_frac", [0.0, 0.4, 1.0])
+@pytest.mark.parametrize("q_len", [1, 23])
+def test_p10_results_do_not_depend_on_residency(resident_frac, q_len):
+    # the same keys, housed as one pool or as bank + backing pool (the backing copies of resident pages poisoned):
+    # identical indices, identical outputs
+    w, x, xb = _bank_case(resident_frac, q_len, 31)
+    Q, K, V, table, lens = _np(x, "Q", "K", "V", "page_table", "kv_lens")
+    Kb, Vb, kback, vback, tb = _np(xb, "K", "V", "k_backing", "v_backing", "page_table")
+    assert ((tb >= 0) == (xb["resident"] | (tb == 0))).all() and (tb < 0).any() == (resident_frac < 1.0)
+    common = dict(kv_lens=lens, page_size=w.page_size, n_sink=2, n_window=3)
+    p = Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk, page_table=table, **common)
+    pb = Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk, page_table=tb,
+                 k_backing=kback, v_backing=vback, **common)
+    idx, idx_b = oracle.mask_estimate(p, Q, K), oracle.mask_estimate(pb, Q, Kb)
+    assert np.array_equal(idx, idx_b)
+    assert np.array_equal(oracle.sparse_attn(p, Q, K, V, idx), oracle.sparse_attn(pb, Q, Kb, Vb, idx_b))
+
+
+@pytest.mark.parametrize("q_len,rep_pos,b_sk", [(1, 0, 1), (23, 0, 1), (23, 2, 2), (1, 1, 1)])
+def test_p10_pages_read_by_mask_estimation(q_len, rep_pos, b_sk):
+    # the map must hold exactly the pages of the representative blocks that the literal transcription scores
+    # (units whose visible blocks all fit are dense and read nothing)
+    w, x, xb = _bank_case(0.5, q_len, 32)
+    Q, lens = _np(x, "Q", "kv_lens")
+    Kb, kback, tb = _np(xb, "K", "k_backing", "page_table")
+    touched = np.zeros(tb.shape, np.uint8)
+    pb = Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk, kv_lens=lens,
+                 page_table=tb, page_size=w.page_size, k_backing=kback, touched=touched, rep_pos=rep_pos, b_sk=b_sk)
+    oracle.mask_estimate(pb, Q, Kb)
+    want = np.zeros_like(touched)
+    Kc = np.zeros((w.batch, w.n_kv_heads, w.kv_len, w.head_dim), np.float32)   # the logical sequences, for the literal run
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            Kc[b, h, :lens[b]] = synth.kv_sequence(w, "k", b, h, int(lens[b])).numpy()
+    pc = Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk, kv_lens=lens)
+    for b, h, qb in oracle.all_units(pc):
+        kv_len = int(lens[b])
+        L = min(kv_len, kv_len - w.q_len + min((qb + 1) * w.bq, w.q_len))
+        if L <= 0 or -(-L // w.bk) <= w.kb:
+            continue
+        scored = []
+        _literal_indices(pc, Q, Kc, b, h, qb, kv_len, 1, b_sk, rep_pos, scored)
+        for r1 in scored:
+            want[b, (r1 - 1) * w.bk // w.page_size] = 1
+    assert want.any() and np.array_equal(touched, want)
+
+
+@pytest.mark.parametrize("q_len,n_sink,n_window", [(1, 0, 0), (1, 3, 9), (23, 0, 0), (23, 5, 2), (23, 0, 30)])
+def test_p10_pages_read_by_sparse_attention(q_len, n_sink, n_window):
+    # the map must hold exactly the pages of the keys in the rows' key sets (written out here from the
+    # definition: selected blocks cut to the visible keys, first n_sink keys, n_window most recent keys)
+    w, x, xb = _bank_case(0.5, q_len, 33)
+    rng = np.random.default_rng(7)
+    Q, lens = _np(x, "Q", "kv_lens")
+    Kb, Vb, kback, vback, tb = _np(xb, "K", "V", "k_backing", "v_backing", "page_table")
+    nqb = -(-w.q_len // w.bq)
+    # arbitrary index sets, some blocks in the future of their rows, some sentinels
+    idx = np.sort(rng.integers(0, w.kv_len // w.bk, (w.batch, w.n_q_heads, nqb, w.kb)) * w.bk, axis=-1).astype(np.int32)
+    idx[rng.random(idx.shape) < 0.2] = SENTINEL
+    touched = np.zeros(tb.shape, np.uint8)
+    pb = Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk, kv_lens=lens,
+                 page_table=tb, page_size=w.page_size, k_backing=kback, v_backing=vback, touched=touched,
+                 n_sink=n_sink, n_window=n_window)
+    oracle.sparse_attn(pb, Q, Kb, Vb, idx)
+    want = np.zeros_like(touched)
+    for b in range(w.batch):
+        for h in range(w.n_q_heads):
+            for i in range(w.q_len):
+                pos = int(lens[b]) - w.q_len + i
+                if pos < 0:
+                    continue
+                keys = {int(f) + n for f in idx[b, h, i // w.bq] if f != SENTINEL for n in range(w.bk)}
+                keys |= set(range(n_sink)) | set(range(pos - n_window + 1, pos + 1))
+                for t in keys:
+                    if 0 <= t <= pos and t < lens[b]:
+                        want[b, t // w.page_size] = 1
+    assert want.any() and np.array_equal(touched, want)
