@@ -47,9 +47,12 @@ __device__ __forceinline__ float max_half_swap(float v)
 // LB = log2(key rows scored per block) = log2(bk / b_sk)
 // SPLIT: the workgroup takes ONE work item; its four waves share the node state, score a quarter of the tiles
 // each and run the selection redundantly (for launches with too few work items to fill the GPU wave by wave)
-template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false>
+// DIRECT: the key rows go from memory straight into LDS (global_load_lds_dwordx4) instead of through registers and
+// ds_write; see the tile loop.  One query tile, 512 branch slots, contiguous K only.
+template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
+    static_assert(!DIRECT || (MT == 1 && E == 8 && !PAGED && !SPLIT), "the direct-to-LDS variant covers one configuration");
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
     constexpr int BK = 1 << LB;    // key rows scored per representative block
@@ -62,20 +65,21 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     static_assert(SPL >= 1, "bk too large for this kernel");
     constexpr int NC = SPLIT ? 1 : 4;  // copies of the per-work-item state
     __shared__ uint32_t keys_s[NC][NB];
-    __shared__ int nds[NC][NB / 2], nde[NC][NB / 2];                   // node ranges [s, e) in key blocks
     __shared__ __attribute__((aligned(16))) int brt_s[NC][NB];        // per branch slot: first key of its centre block, -1 = empty
     // List rounds: slot of the i-th block still to be scored.  With 1024 branch slots and one query tile the
     // slot is packed into the list entry instead (slot << 21 | block index; the launcher checks that block
     // indices fit 21 bits): without this array the workgroup's LDS is 80 KB and two workgroups share a
     // compute unit.
-    constexpr bool PACK = E == 16 && MT == 1;
-    __shared__ int fsl_s[PACK ? 1 : NC][PACK ? 1 : NB / 2];
+    constexpr bool PACK = (E == 16 || DIRECT) && MT == 1;
     // With a page table: the page of every branch slot's block, looked up when the branch table is written
     // (once per round) so that the tile loop has no dependent look-up.  With 2048 slots the table does not
     // fit; the look-up is then issued from the tile loop, a few tiles ahead of the row loads.
     constexpr bool PGL = PAGED && E <= 16;
-    __shared__ __attribute__((aligned(16))) int bpg_s[PGL ? NC : 1][PGL ? NB : 1];
-    __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][32 * D * 2 / 16];  // one 32-row tile per wave
+    // one 32-row tile per wave.  DIRECT: the node ranges [s, e) share it (they are only touched between two rounds'
+    // tile loops and sit in registers meanwhile); the workgroup's LDS is then 48 KB and three workgroups fit a
+    // compute unit.
+    constexpr int TILEB = 32 * D * 2;
+    __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][TILEB / 16];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
@@ -130,7 +134,23 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     }
 
     uint32_t *keys = keys_s[own];
-    int *ns = nds[own], *ne = nde[own], *brt = brt_s[own], *fsl = fsl_s[PACK ? 0 : own], *bpg = bpg_s[PGL ? own : 0];
+    int *ns, *ne, *brt = brt_s[own], *fsl = nullptr, *bpg = nullptr;
+    if constexpr (DIRECT) {
+        ns = (int *)tile_buf[wave];
+        ne = ns + NB / 2;
+    } else {
+        __shared__ int nds[NC][NB / 2], nde[NC][NB / 2];  // node ranges [s, e) in key blocks
+        ns = nds[own];
+        ne = nde[own];
+    }
+    if constexpr (!PACK) {
+        __shared__ int fsl_s[NC][NB / 2];
+        fsl = fsl_s[own];
+    }
+    if constexpr (PGL) {
+        __shared__ __attribute__((aligned(16))) int bpg_s[NC][NB];
+        bpg = bpg_s[own];
+    }
     // (page sizes are powers of two here: no branch or division in the tile loop)
     const int *ptab = PAGED ? p.page_table + (int64_t)b * p.max_pages : nullptr;
     const int pg0 = PGL ? ptab[0] : 0;  // empty entries load key 0
@@ -344,6 +364,12 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    if constexpr (DIRECT) {
+        // The query loads end here, where the compiler can see it: it does not count the loads that the tile loop
+        // issues from inline assembly, and a wait for a query fragment left inside that loop would wait for them.
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) asm volatile("" :: "v"(qf[0][kk]));
+    }
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         // Pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two.
         // The loop body is straight-line code: tile numbers past the end are clamped to the last tile
@@ -353,6 +379,85 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         // With SPLIT, wave w takes tiles w, w + 4, ...: tile_of(i) is the i-th tile of this wave.
         const int nt_all = __builtin_amdgcn_readfirstlane(n_tiles);
         const int nt = SPLIT ? (nt_all > wave ? (nt_all - wave + 3) >> 2 : 0) : nt_all;
+        if constexpr (DIRECT) {
+            // Direct-to-LDS variant: a global load that delivers into LDS (lane l's 16 bytes land at M0 + 16 l)
+            // needs neither staging registers nor a ds_write, so this variant runs in 160 registers and 48 KB of
+            // LDS: three waves per SIMD instead of two.  Load j of a tile fills LDS rows 4j .. 4j+3; lane group
+            // lg = l / 16 supplies tile row lg * 8 + j (the rows a lane loads belong to consecutive branch slots,
+            // as in the other variant), and the XOR swizzle is applied to the global chunk a lane fetches.  The
+            // wave has one tile buffer: as soon as a tile's operands are in registers the buffer is refilled with
+            // the next tile, which lands while this one is multiplied and scored.  The loads are inline assembly
+            // with explicit waits: the compiler neither sees that they write LDS nor counts them, and no other
+            // vector memory instruction is issued inside the loop.
+            int sv[E];  // node ranges, out of the way of the tiles
+#pragma unroll
+            for (int i = 0; i < E / 2; ++i) { sv[i] = ns[i * 64 + lane]; sv[E / 2 + i] = ne[i * 64 + lane]; }
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            if (nt > 0) {
+                const int last_tile = nt - 1;
+                auto tile_of = [&](int i) __attribute__((always_inline)) { return min(i, last_tile); };
+                const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)tile_buf[wave];
+                const int last = kv_len - 1;
+                // one load: row j of this lane's share of the tile described by mt_, into buffer `buf`
+                auto issue_row = [&](const meta_t &mt_, int buf, int j) __attribute__((always_inline)) {
+                    const int i = j / BK, n = j % BK;
+                    const int tf = max(mt_.m[i], 0);
+                    const int rho = lg * NLD + j;
+                    const uint32_t voff = __umul24((uint32_t)min(tf + (n << ks), last), row_bytes) +
+                                          (uint32_t)((lc ^ (rho & (CPR - 1))) << 4);
+                    const uint32_t dst = __builtin_amdgcn_readfirstlane(ring + buf * TILEB + j * 1024);
+                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                                 :: "v"(voff), "s"(Kseq), "s"(dst) : "memory", "m0");
+                };
+                // operands of the tile in buffer `buf`: tile row `col` sits in LDS row 4 (col % 8) + col / 8
+                auto read_operands = [&](int buf, uint4 (&kv)[KS]) __attribute__((always_inline)) {
+                    const uint32_t base = ring + buf * TILEB + (RPI * (col % NLD) + col / NLD) * ROWB;
+#pragma unroll
+                    for (int kk = 0; kk < KS; ++kk)
+                        asm volatile("ds_read_b128 %0, %1" : "=v"(kv[kk]) : "v"(base + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4)) : "memory");
+                };
+                // One step: the tile in the buffer is multiplied and, as soon as its operands are in registers,
+                // the buffer is refilled with the next tile (described by mt_, whose row info comes back in t / slot).
+                auto step = [&](acc_t &A, meta_t &mt_, int &t, int &slot, int next_meta_tile) __attribute__((always_inline)) {
+                    f32x16 (&acc)[MT] = A.a;
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tile has landed
+                    uint4 kv[KS];
+                    read_operands(0, kv);
+                    row_info(mt_, t, slot);
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // operands are in registers: the buffer may be refilled
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int kk = 0; kk < KS; ++kk) {
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][kk], __builtin_bit_cast(bf16x8, kv[kk]), kk == 0 ? zero : acc[0], 0, 0, 0);
+                        issue_row(mt_, 0, kk);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    read_meta(next_meta_tile, mt_);
+                };
+                meta_t m0, m1;
+                int tc, sc, tn, sn;
+                read_meta(tile_of(0), m0);
+                read_meta(tile_of(1), m1);
+                row_info(m0, tc, sc);
+#pragma unroll
+                for (int j = 0; j < NLD; ++j) issue_row(m0, 0, j);
+                read_meta(tile_of(2), m0);
+                for (int tile = 0; tile < nt; tile += 2) {
+                    // here: the buffer holds (or is receiving) tile `tile` (row info tc/sc); m1 and m0 hold the
+                    // branch-table entries of tile+1 and tile+2
+                    acc_t A;
+                    step(A, m1, tn, sn, tile_of(tile + 3));
+                    score_finish(A, tc, sc);
+                    acc_t B;
+                    step(B, m0, tc, sc, tile_of(tile + 4));
+                    score_finish(B, tn, sn);
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+#pragma unroll
+            for (int i = 0; i < E / 2; ++i) { ns[i * 64 + lane] = sv[i]; ne[i * 64 + lane] = sv[E / 2 + i]; }
+        } else
         if (nt > 0) {
             const int last_tile = nt - 1;
             auto tile_of = [&](int i) __attribute__((always_inline)) { return SPLIT ? wave + 4 * min(i, last_tile) : min(i, last_tile); };
@@ -474,6 +579,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 {
     mask_mfma_body<1, E, D, PAGED, LB>(p, xcd_map);
 }
+// The same with direct-to-LDS loads (head dim 128, k/bk <= 256, contiguous K, block indices below 2^21)
+template <int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, 8, 128, false, LB, false, true>(p, xcd_map);
+}
 template <int E, int D, bool PAGED, int LB>
 __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int xcd_map)
 {
@@ -518,7 +629,11 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
             else HIPATTN_LAUNCH(mask_mfma_kernel_q64_split, 16);
         }
     } else if constexpr (MT == 1) {
-        if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
+        // (contexts whose keys stay in the caches: beyond that the kernel waits on memory and the deeper
+        // prefetch of the register-staged variant is worth more than the third wave)
+        if (D == 128 && p.kb <= 256 && !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20))
+            hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<LB>), grid, block, 0, st, p, xcd_map);
+        else if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
         else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
         else HIPATTN_LAUNCH(mask_mfma_kernel_q32_wide, 32);
     } else {
