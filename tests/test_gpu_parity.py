@@ -516,6 +516,26 @@ def test_token_bank_in_host_memory():
 
 
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
+def test_direct_to_lds_variant_limits(integer):
+    # the mask kernel with direct-to-LDS loads serves contiguous K of up to 16 MB per kv head (64k keys at head dim 128):
+    # the largest context it takes, the first one it leaves to the register-staged kernel, a short last key block, list
+    # rounds (first / last representative), key sampling and a ragged batch
+    w = synth.Workload("direct_64k", 1, 4, 1, 128, 8192, 65536, 512, 32, 2, "bf16", rho=0.95, spike_every=8192,
+                       integer=integer, seed=131)
+    nqb = w.n_query_blocks
+    units = [(0, h, qb) for h in range(4) for qb in (0, 1, 77, nqb // 2, nqb - 2, nqb - 1)]
+    U.run_case(w, 0, units=units)
+    U.run_case(synth.scaled(w, kv_len=65536 + 64), 0, units=units)
+    U.run_case(synth.scaled(w, kv_len=40001, q_len=9001), 0, units=[(0, h, qb) for h in range(4) for qb in (0, 100, 281)], rep_pos=2)
+    U.run_case(synth.scaled(w, kv_len=30000, q_len=30000, bk=4, k=1024), 0,
+               units=[(0, h, qb) for h in range(4) for qb in (0, 31, 32, 33, 500, 937)], rep_pos=1, b_sk=2, n_window=17)
+    wr = synth.Workload("direct_ragged", 3, 4, 2, 128, 3000, 9000, 256, 32, 2, "bf16", rho=0.9, ragged=(3500, 9000),
+                        integer=integer, seed=132)
+    nqb = wr.n_query_blocks
+    U.run_case(wr, 0, units=[(b, h, qb) for b in range(3) for h in range(4) for qb in (0, 40, nqb - 1)])
+
+
+@pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_blocks_of_8_and_16_keys(integer):
     # bk = 8 (8 scored rows per block) and bk = 16 with b_sk = 2 on the tuned kernels: prefill at head dim 128,
     # decode (mask with 8 rows per block; attention walks the blocks as pieces of 4 rows)
