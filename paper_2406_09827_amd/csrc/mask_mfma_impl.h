@@ -52,7 +52,7 @@ __device__ __forceinline__ float max_half_swap(float v)
 template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
-    static_assert(!DIRECT || (MT == 1 && E == 8 && !PAGED && !SPLIT), "the direct-to-LDS variant covers one configuration");
+    static_assert(!DIRECT || (MT == 1 && E == 8 && !PAGED && !SPLIT), "the direct-to-LDS variant: one query tile, 512 slots, contiguous K");
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
     constexpr int BK = 1 << LB;    // key rows scored per representative block
@@ -382,13 +382,14 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         if constexpr (DIRECT) {
             // Direct-to-LDS variant: a global load that delivers into LDS (lane l's 16 bytes land at M0 + 16 l)
             // needs neither staging registers nor a ds_write, so this variant runs in 160 registers and 48 KB of
-            // LDS: three waves per SIMD instead of two.  Load j of a tile fills LDS rows 4j .. 4j+3; lane group
-            // lg = l / 16 supplies tile row lg * 8 + j (the rows a lane loads belong to consecutive branch slots,
-            // as in the other variant), and the XOR swizzle is applied to the global chunk a lane fetches.  The
-            // wave has one tile buffer: as soon as a tile's operands are in registers the buffer is refilled with
-            // the next tile, which lands while this one is multiplied and scored.  The loads are inline assembly
-            // with explicit waits: the compiler neither sees that they write LDS nor counts them, and no other
-            // vector memory instruction is issued inside the loop.
+            // LDS (head dim 128): three waves per SIMD instead of two.  Load j of a tile fills 1 KB of LDS, i.e. LDS
+            // rows RPI j .. RPI j + RPI - 1 (RPI = 4 rows of 256 bytes, or 8 of 128); lane group lg supplies tile
+            // row lg * NLD + j (the rows a lane loads belong to consecutive branch slots, as in the other variant),
+            // so tile row r sits in LDS row RPI (r % NLD) + r / NLD, and the XOR swizzle is applied to the global
+            // chunk a lane fetches.  The wave has one tile buffer: as soon as a tile's operands are in registers the
+            // buffer is refilled with the next tile, which lands while this one is multiplied and scored.  The loads
+            // are inline assembly with explicit waits: the compiler neither sees that they write LDS nor counts
+            // them, and no other vector memory instruction is issued inside the loop.
             int sv[E];  // node ranges, out of the way of the tiles
 #pragma unroll
             for (int i = 0; i < E / 2; ++i) { sv[i] = ns[i * 64 + lane]; sv[E / 2 + i] = ne[i * 64 + lane]; }
@@ -409,7 +410,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                                  :: "v"(voff), "s"(Kseq), "s"(dst) : "memory", "m0");
                 };
-                // operands of the tile in buffer `buf`: tile row `col` sits in LDS row 4 (col % 8) + col / 8
+                // operands of the tile in buffer `buf`: tile row `col` sits in LDS row RPI (col % NLD) + col / NLD
                 auto read_operands = [&](int buf, uint4 (&kv)[KS]) __attribute__((always_inline)) {
                     const uint32_t base = ring + buf * TILEB + (RPI * (col % NLD) + col / NLD) * ROWB;
 #pragma unroll
@@ -579,11 +580,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 {
     mask_mfma_body<1, E, D, PAGED, LB>(p, xcd_map);
 }
-// The same with direct-to-LDS loads (head dim 128, k/bk <= 256, contiguous K, block indices below 2^21)
-template <int LB>
+// The same with direct-to-LDS loads (k/bk <= 256, contiguous K, block indices below 2^21)
+template <int D, int LB>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct(KParams p, int xcd_map)
 {
-    mask_mfma_body<1, 8, 128, false, LB, false, true>(p, xcd_map);
+    mask_mfma_body<1, 8, D, false, LB, false, true>(p, xcd_map);
 }
 template <int E, int D, bool PAGED, int LB>
 __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int xcd_map)
@@ -631,8 +632,8 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
     } else if constexpr (MT == 1) {
         // (contexts whose keys stay in the caches: beyond that the kernel waits on memory and the deeper
         // prefetch of the register-staged variant is worth more than the third wave)
-        if (D == 128 && p.kb <= 256 && !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20))
-            hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<LB>), grid, block, 0, st, p, xcd_map);
+        if (p.kb <= 256 && !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20))
+            hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
         else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
         else HIPATTN_LAUNCH(mask_mfma_kernel_q32_wide, 32);
