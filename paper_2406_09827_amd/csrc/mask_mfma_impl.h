@@ -52,7 +52,7 @@ __device__ __forceinline__ float max_half_swap(float v)
 template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
-    static_assert(!DIRECT || (MT == 1 && E == 8 && !PAGED && !SPLIT), "the direct-to-LDS variant: one query tile, 512 slots, contiguous K");
+    static_assert(!DIRECT || (MT == 1 && E <= 16 && !PAGED && !SPLIT), "the direct-to-LDS variant: one query tile, up to 1024 slots, contiguous K");
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
     constexpr int BK = 1 << LB;    // key rows scored per representative block
@@ -580,11 +580,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
 {
     mask_mfma_body<1, E, D, PAGED, LB>(p, xcd_map);
 }
-// The same with direct-to-LDS loads (k/bk <= 256, contiguous K, block indices below 2^21)
+// The same with direct-to-LDS loads (contiguous K, block indices below 2^21): three waves per SIMD with 512 branch
+// slots (k/bk <= 256), two with 1024 (k/bk <= 512; the register-staged kernel runs one there)
 template <int D, int LB>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct(KParams p, int xcd_map)
 {
     mask_mfma_body<1, 8, D, false, LB, false, true>(p, xcd_map);
+}
+template <int D, int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void mask_mfma_kernel_q32_direct_1k(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, 16, D, false, LB, false, true>(p, xcd_map);
 }
 template <int E, int D, bool PAGED, int LB>
 __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q64(KParams p, int xcd_map)
@@ -632,8 +638,9 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
     } else if constexpr (MT == 1) {
         // (contexts whose keys stay in the caches: beyond that the kernel waits on memory and the deeper
         // prefetch of the register-staged variant is worth more than the third wave)
-        if (p.kb <= 256 && !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20))
-            hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
+        const bool direct = !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
+        if (direct && p.kb <= 256) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
+        else if (direct && p.kb <= 512) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_1k<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
         else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
         else HIPATTN_LAUNCH(mask_mfma_kernel_q32_wide, 32);
