@@ -80,6 +80,8 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // compute unit.
     constexpr int TILEB = 32 * D * 2;
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][TILEB / 16];
+    // (the LDS address of a direct load travels in M0: all of this variant's LDS stays below 64 KB)
+    static_assert(!DIRECT || 2 * NC * NB * 4 + 4 * TILEB <= 65536, "LDS of the direct-to-LDS variant");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
