@@ -52,7 +52,7 @@ __device__ __forceinline__ float max_half_swap(float v)
 template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
-    static_assert(!DIRECT || (MT == 1 && E <= 16 && !PAGED && !SPLIT), "the direct-to-LDS variant: one query tile, up to 1024 slots, contiguous K");
+    static_assert(!DIRECT || (MT == 1 && E <= 16 && !SPLIT && (!PAGED || E == 8)), "the direct-to-LDS variant: one query tile, up to 1024 slots (512 over a paged pool)");
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
     constexpr int BK = 1 << LB;    // key rows scored per representative block
@@ -74,14 +74,20 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // With a page table: the page of every branch slot's block, looked up when the branch table is written
     // (once per round) so that the tile loop has no dependent look-up.  With 2048 slots the table does not
     // fit; the look-up is then issued from the tile loop, a few tiles ahead of the row loads.
-    constexpr bool PGL = PAGED && E <= 16;
+    constexpr bool PGL = PAGED && E <= 16 && !DIRECT;
+    // DIRECT over a paged pool: the sequence's row of the page table (at most 1024 pages) is copied into LDS once per
+    // workgroup - the launcher sees to it that the four work items of a workgroup belong to one sequence - and the
+    // tile loop looks pages up there: 4 KB instead of the 8 KB of per-slot page ids, which keeps three workgroups
+    // on a compute unit.
+    constexpr bool PTC = PAGED && DIRECT;
+    constexpr int kMaxCachedPages = 1024;
     // one 32-row tile per wave.  DIRECT: the node ranges [s, e) share it (they are only touched between two rounds'
     // tile loops and sit in registers meanwhile); the workgroup's LDS is then 48 KB and three workgroups fit a
     // compute unit.
     constexpr int TILEB = 32 * D * 2;
     __shared__ __attribute__((aligned(16))) uint4 tile_buf[4][TILEB / 16];
     // (the LDS address of a direct load travels in M0: all of this variant's LDS stays below 64 KB)
-    static_assert(!DIRECT || 2 * NC * NB * 4 + 4 * TILEB <= 65536, "LDS of the direct-to-LDS variant");
+    static_assert(!DIRECT || 2 * NC * NB * 4 + 4 * TILEB + (PTC ? 4 * kMaxCachedPages : 0) <= 65536, "LDS of the direct-to-LDS variant");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hh = lane >> 5;
@@ -156,6 +162,13 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // (page sizes are powers of two here: no branch or division in the tile loop)
     const int *ptab = PAGED ? p.page_table + (int64_t)b * p.max_pages : nullptr;
     const int pg0 = PGL ? ptab[0] : 0;  // empty entries load key 0
+    int *ptc = nullptr;
+    if constexpr (PTC) {
+        // every wave of the workgroup writes the same values: no workgroup barrier (waves may have left already)
+        __shared__ int ptab_s[kMaxCachedPages];
+        ptc = ptab_s;
+        for (int i = lane; i < p.max_pages; i += 64) ptc[i] = ptab[i];
+    }
     // branch-table entry i: first key `t0` of the block to score (-1: none); `word` is what the table holds
     auto set_branch = [&](int i, int word, int t0) __attribute__((always_inline)) {
         brt[i] = word;
@@ -252,6 +265,9 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     mt_.pg[i] = v.x; mt_.pg[i + 1] = v.y; mt_.pg[i + 2] = v.z; mt_.pg[i + 3] = v.w;
                 }
             }
+        } else if (PTC) {
+#pragma unroll
+            for (int i = 0; i < SPL; ++i) mt_.pg[i] = ptc[max(mt_.m[i], 0) >> p.page_shift];
         } else if (PAGED) {
 #pragma unroll
             for (int i = 0; i < SPL; ++i) mt_.pg[i] = ptab[max(mt_.m[i], 0) >> p.page_shift];
@@ -406,11 +422,20 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     const int i = j / BK, n = j % BK;
                     const int tf = max(mt_.m[i], 0);
                     const int rho = lg * NLD + j;
-                    const uint32_t voff = __umul24((uint32_t)min(tf + (n << ks), last), row_bytes) +
-                                          (uint32_t)((lc ^ (rho & (CPR - 1))) << 4);
+                    const uint32_t chunk = (uint32_t)((lc ^ (rho & (CPR - 1))) << 4);
                     const uint32_t dst = __builtin_amdgcn_readfirstlane(ring + buf * TILEB + j * 1024);
-                    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                                 :: "v"(voff), "s"(Kseq), "s"(dst) : "memory", "m0");
+                    if constexpr (PAGED) {
+                        // page base (the resident pool, or the backing pool for a negative entry) plus a 32-bit offset inside the page
+                        const uint32_t r = (uint32_t)((tf & (p.page_size - 1)) + min(tf + (n << ks), last) - tf);
+                        const char *src = (mt_.pg[i] < 0 ? Kpool_back : Kpool) + (uint64_t)(uint32_t)page_in_pool(mt_.pg[i]) * page_bytes +
+                                          (__umul24(r, row_bytes) + chunk);
+                        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                                     :: "v"(src), "s"(dst) : "memory", "m0");
+                    } else {
+                        const uint32_t voff = __umul24((uint32_t)min(tf + (n << ks), last), row_bytes) + chunk;
+                        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                                     :: "v"(voff), "s"(Kseq), "s"(dst) : "memory", "m0");
+                    }
                 };
                 // operands of the tile in buffer `buf`: tile row `col` sits in LDS row RPI (col % NLD) + col / NLD
                 auto read_operands = [&](int buf, uint4 (&kv)[KS]) __attribute__((always_inline)) {
@@ -590,6 +615,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
     mask_mfma_body<1, 8, D, false, LB, false, true>(p, xcd_map);
 }
 template <int D, int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct_paged(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, 8, D, true, LB, false, true>(p, xcd_map);
+}
+template <int D, int LB>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void mask_mfma_kernel_q32_direct_1k(KParams p, int xcd_map)
 {
     mask_mfma_body<1, 16, D, false, LB, false, true>(p, xcd_map);
@@ -619,7 +649,7 @@ __global__ __launch_bounds__(kThreads) void mask_mfma_kernel_q32_wide(KParams p,
 }
 
 template <int MT, int D, int LB>
-static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, bool split, hipStream_t st)
+static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, bool split, bool one_sequence_per_workgroup, hipStream_t st)
 {
     dim3 block(kThreads);
     // the page-table variant is a separate instantiation: a table read in the row-offset code
@@ -641,7 +671,10 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
         // (contexts whose keys stay in the caches: beyond that the kernel waits on memory and the deeper
         // prefetch of the register-staged variant is worth more than the third wave)
         const bool direct = !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
-        if (direct && p.kb <= 256) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
+        const bool direct_paged = p.page_table && p.kb <= 256 && p.max_pages <= 1024 && one_sequence_per_workgroup &&
+                                  (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
+        if (direct_paged) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_paged<D, LB>), grid, block, 0, st, p, xcd_map);
+        else if (direct && p.kb <= 256) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (direct && p.kb <= 512) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_1k<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
         else if (p.kb <= 512) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 16);
@@ -669,10 +702,12 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 2) : 0;
     dim3 grid((unsigned)placed_workgroups(xcd_map, split ? 1 : 4, per_group, groups));
     const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
+    // the four work items of a workgroup are consecutive items of one (sequence, kv head) group
+    const bool one_seq = !split && per_group % 4 == 0;
     if constexpr (LB <= 2) {  // (with 64 channels a lane loads 4 rows of a tile, fewer than an 8-row block)
-        if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, split, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, split, st);
+        if (p.d == 64) return one_tile ? launch_mask_mfma_e<1, 64, LB>(p, xcd_map, grid, split, one_seq, st) : launch_mask_mfma_e<2, 64, LB>(p, xcd_map, grid, split, one_seq, st);
     }
-    return one_tile ? launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, split, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, split, st);
+    return one_tile ? launch_mask_mfma_e<1, 128, LB>(p, xcd_map, grid, split, one_seq, st) : launch_mask_mfma_e<2, 128, LB>(p, xcd_map, grid, split, one_seq, st);
 }
 
 }  // namespace hipattn
