@@ -473,6 +473,14 @@ def test_paged_prefill_variants(integer):
     U.run_case(synth.scaled(w, q_len=64, page_size=8), 0)
     U.run_case(synth.scaled(w, q_len=64, k=1024, page_size=8), 0, rep_pos=2)
     U.run_case(synth.scaled(w, q_len=96, k=1024, bq=64, page_size=8, head_dim=64), 0, rep_pos=1)
+    # four query heads per kv head: the four work items of a workgroup share a sequence, which the variant with the page
+    # table cached in LDS needs; with 8-key pages the table (1129 pages) is too long for it
+    w4 = synth.scaled(w, n_q_heads=8, n_kv_heads=2)
+    units4 = [(b, h, qb) for b in range(2) for h in (0, 3, 4, 7) for qb in (0, 15, 16, 70, nqb // 2, nqb - 1)]
+    for rep_pos in (0, 2):
+        U.run_case(w4, 0, units=units4, rep_pos=rep_pos, n_window=9)
+    U.run_case(synth.scaled(w4, page_size=8), 0, units=units4)
+    U.run_case(synth.scaled(w4, head_dim=64, page_size=16, bk=4, k=1024), 0, units=units4, b_sk=2)
     U.run_case(synth.scaled(w, page_size=48), 0, units=units)
     U.run_case(synth.scaled(w, page_size=6, batch=1), 0, units=[u for u in units if u[0] == 0], rep_pos=2)
 
