@@ -3,10 +3,10 @@
 
 namespace hipattn {
 
-extern template hipError_t launch_mask_decode_variant<false, 64>(const KParams &, hipStream_t);
-extern template hipError_t launch_mask_decode_variant<false, 128>(const KParams &, hipStream_t);
-extern template hipError_t launch_mask_decode_variant<true, 64>(const KParams &, hipStream_t);
-extern template hipError_t launch_mask_decode_variant<true, 128>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<64, false>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<64, true>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<128, false>(const KParams &, hipStream_t);
+extern template hipError_t launch_mask_decode_variant<128, true>(const KParams &, hipStream_t);
 
 bool mask_decode_supported(const KParams &p, bool bf16)
 {
@@ -16,9 +16,9 @@ bool mask_decode_supported(const KParams &p, bool bf16)
 
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st)
 {
-    // first / last representative: the variant that carries a node's score to the child sharing its representative
-    if (p.rep_pos != 0) return p.d == 64 ? launch_mask_decode_variant<true, 64>(p, st) : launch_mask_decode_variant<true, 128>(p, st);
-    return p.d == 64 ? launch_mask_decode_variant<false, 64>(p, st) : launch_mask_decode_variant<false, 128>(p, st);
+    const bool wide = p.bk / p.b_sk >= 4;
+    if (p.d == 64) return wide ? launch_mask_decode_variant<64, true>(p, st) : launch_mask_decode_variant<64, false>(p, st);
+    return wide ? launch_mask_decode_variant<128, true>(p, st) : launch_mask_decode_variant<128, false>(p, st);
 }
 
 }  // namespace hipattn

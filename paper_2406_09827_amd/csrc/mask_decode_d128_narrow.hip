@@ -1,0 +1,6 @@
+// Instantiates the decode mask-estimation kernels: head dim 128, 1 or 2 scored key rows per block.
+#include "mask_decode_impl.h"
+
+namespace hipattn {
+template hipError_t launch_mask_decode_variant<128, false>(const KParams &, hipStream_t);
+}  // namespace hipattn

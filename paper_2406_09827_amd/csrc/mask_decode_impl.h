@@ -16,7 +16,9 @@
 //   * with the first or the last block as representative, one child of every node has the
 //     node's own representative (left child / first block, right child / last block): its score is
 //     the score that selected the node, carried over as a key, and from the second round on only the
-//     other child is gathered and scored - about half the memory traffic.
+//     other child is gathered and scored - about half the memory traffic.  With the centre representative
+//     the same holds in the final round (every node one or two blocks long: a one-block node is its own
+//     representative, the right half of a two-block node is the node's): only the left halves are scored.
 // Ragged lengths (kv_lens) and a page table are handled per row.
 #pragma once
 #include "common.h"
@@ -29,9 +31,7 @@ namespace hipattn {
 //                branches each (stage i goes to wave i % 4), meet at a barrier, run the selection
 //                redundantly and write a quarter of the survivors each.  Used at small batch,
 //                where one wave per SIMD cannot keep enough loads in flight.
-// CARRY = true is the variant for a first / last representative block (scores carried from parent to child);
-// it is a separate instantiation so that the default (centre) path carries none of its bookkeeping.
-template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT, bool CARRY>
+template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xcd_map)
 {
     constexpr int NB = 64 * E;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     constexpr int WS = SPLIT ? 4 : 1;  // waves sharing one problem
     __shared__ uint32_t keys_s[NW][NB];
     __shared__ int nds[NW][2][NB / 2], nde[NW][2][NB / 2];
-    __shared__ uint32_t nkey_s[CARRY ? NW : 1][2][CARRY ? NB / 2 : 1];  // score key of the branch that became each node
+    __shared__ uint32_t nkey_s[NW][2][NB / 2];  // score key of the branch that became each node
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // (uniform: what follows from it stays in scalar registers)
     const int grp = lane / LPR, lc = lane % LPR;
@@ -95,13 +95,16 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     const bf16_t *Kbase = (const bf16_t *)p.K;
     const int64_t back_delta = (const bf16_t *)p.Kback - Kbase;  // elements from the resident pool to the backing pool
     int cur = 0;
-    bool carry = false;  // set after the first iteration, unless the centre block represents a branch
+    bool carry = false;  // a round in which one child of every node keeps the node's score (never the first round)
     // side of a node's children that is scored in a carry round: the left one when the LAST block
     // represents (the right child ends where the node ends), the right one for FIRST
-    const int side = p.rep_pos == 2 ? 0 : 1;
+    // (with the centre representative only the final round carries: there every node is one or two blocks long, a
+    // one-block node is its own representative and the right half of a two-block node is the node's representative,
+    // so the left children alone are scored)
+    const int side = p.rep_pos == 1 ? 1 : 0;
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
         const int *ns = nds[own][cur], *ne = nde[own][cur];
-        const uint32_t *nkey = nkey_s[CARRY ? own : 0][CARRY ? cur : 0];
+        const uint32_t *nkey = nkey_s[own][cur];
         // work items of the scoring loop: every branch slot, or in a carry round one per node
         const int n_items = carry ? kb : 2 * kb;
 
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
         select_topk_ordered<E>(key, kb, keep, dest);
         int *ns2 = nds[own][cur ^ 1], *ne2 = nde[own][cur ^ 1];
-        uint32_t *nkey2 = nkey_s[CARRY ? own : 0][CARRY ? cur ^ 1 : 0];
+        uint32_t *nkey2 = nkey_s[own][cur ^ 1];
 #pragma unroll
         for (int i = 0; i < E; ++i) {
             if (keep[i] && (!SPLIT || (i & 3) == wave)) {
@@ -209,11 +212,11 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
                 const int mid = s + ((e - s) >> 1);
                 ns2[dest[i]] = (slot & 1) ? mid : s;
                 ne2[dest[i]] = (slot & 1) ? e : mid;
-                if (CARRY) nkey2[dest[i]] = key[i];
+                nkey2[dest[i]] = key[i];
             }
         }
         cur ^= 1;
-        carry = CARRY;
+        carry = p.rep_pos != 0 || ((maxlen + 1) >> 1) == 2;
         sync_problem();
     }
 
@@ -221,14 +224,14 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     for (int j = tix; j < kb; j += tn) out[j] = ns[j] * bk;
 }
 
-template <int BK, int D, int ROWS, bool SPLIT, bool CARRY>
+template <int BK, int D, int ROWS, bool SPLIT>
 static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t st)
 {
     dim3 block(kThreads);
 #define HIPATTN_LAUNCH(EV)                                                                                  \
     do {                                                                                                    \
-        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true, SPLIT, CARRY>), grid, block, 0, st, p, xcd_map);  \
-        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false, SPLIT, CARRY>), grid, block, 0, st, p, xcd_map);       \
+        if (p.page_table) hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, true, SPLIT>), grid, block, 0, st, p, xcd_map);  \
+        else hipLaunchKernelGGL((mask_decode_kernel<EV, BK, D, ROWS, false, SPLIT>), grid, block, 0, st, p, xcd_map);       \
     } while (0)
     if (p.kb <= 128) HIPATTN_LAUNCH(4);
     else if (p.kb <= 256) HIPATTN_LAUNCH(8);
@@ -242,29 +245,27 @@ static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t
 // that enough loads are in flight per compute unit.  Many problems: a wave per problem; shallower
 // stages need fewer registers, so more waves fit a SIMD and hide each other's latency (including the
 // page-table lookups).
-template <int BK, int D, bool CARRY>
+template <int BK, int D>
 static hipError_t launch_e(const KParams &p, hipStream_t st)
 {
     const int64_t problems = (int64_t)p.batch * p.hq;
     if (problems < 2048) {
         const int64_t groups = (int64_t)p.batch * p.hkv;
         const int xcd_map = groups % 8 == 0 ? 1 : 0;
-        return launch_r<BK, D, 8, true, CARRY>(p, dim3((unsigned)problems), xcd_map, st);
+        return launch_r<BK, D, 8, true>(p, dim3((unsigned)problems), xcd_map, st);
     }
     dim3 grid((unsigned)((problems + 3) / 4));
-    if (problems >= 4096) return launch_r<BK, D, 8, false, CARRY>(p, grid, 0, st);
-    return launch_r<BK, D, 16, false, CARRY>(p, grid, 0, st);
+    if (problems >= 4096) return launch_r<BK, D, 8, false>(p, grid, 0, st);
+    return launch_r<BK, D, 16, false>(p, grid, 0, st);
 }
 
-// One translation unit per (variant, head dim) instantiates this.
-template <bool CARRY, int D> hipError_t launch_mask_decode_variant(const KParams &p, hipStream_t st)
+// One translation unit per (head dim, block width) instantiates this: WIDE = 4 or 8 scored rows per block, else 1 or 2.
+template <int D, bool WIDE> hipError_t launch_mask_decode_variant(const KParams &p, hipStream_t st)
 {
     if ((int64_t)p.batch * p.hq == 0) return hipSuccess;
     const int rows = p.bk / p.b_sk;
-    if (rows == 1) return launch_e<1, D, CARRY>(p, st);
-    if (rows == 2) return launch_e<2, D, CARRY>(p, st);
-    if (rows == 4) return launch_e<4, D, CARRY>(p, st);
-    return launch_e<8, D, CARRY>(p, st);
+    if constexpr (WIDE) return rows == 4 ? launch_e<4, D>(p, st) : launch_e<8, D>(p, st);
+    else return rows == 1 ? launch_e<1, D>(p, st) : launch_e<2, D>(p, st);
 }
 
 }  // namespace hipattn
