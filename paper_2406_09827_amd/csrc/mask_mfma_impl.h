@@ -14,7 +14,9 @@
 //     ONE read of the branch table (its rows belong to consecutive branch slots), issued a
 //     further tile ahead, so no LDS round trip sits between two tiles.  Rows of empty
 //     branches load row 0 of the sequence (always mapped) and drop the result: loads stay
-//     unconditional.
+//     unconditional.  For one query tile, up to 1024 branch slots and keys that stay in the caches
+//     (the common prefill shapes) a second form of the loop loads the rows straight into LDS
+//     (global_load_lds_dwordx4): no staging registers, three waves per SIMD instead of two.
 //   * Sampling strides b_sq / b_sk (powers of two) shrink the operand tiles: only the sampled query
 //     rows are loaded into the A operand, only the sampled key rows of a block are gathered.
 //   * v_mfma_f32_32x32x16_bf16 gives a 32(query) x 32(key) score tile; the branch score is
