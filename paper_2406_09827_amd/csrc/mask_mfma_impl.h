@@ -419,7 +419,9 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                 auto tile_of = [&](int i) __attribute__((always_inline)) { return min(i, last_tile); };
                 const uint32_t ring = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)tile_buf[wave];
                 const int last = kv_len - 1;
-                // one load: row j of this lane's share of the tile described by mt_, into buffer `buf`
+                // one load: row j of this lane's share of the tile described by mt_, into buffer `buf`.  (M0 is a
+                // reserved register: the compiler warns that it does not track the clobber.  It is written and
+                // consumed inside one asm statement, and nothing else in these kernels uses M0.)
                 auto issue_row = [&](const meta_t &mt_, int buf, int j) __attribute__((always_inline)) {
                     const int i = j / BK, n = j % BK;
                     const int tf = max(mt_.m[i], 0);
