@@ -1,6 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
 import numpy as np
 import pytest
+import paper_2406_09827_amd as hipattn
 import torch
 
 from paper_2406_09827_amd import synth, FORCE_GENERIC
@@ -513,6 +514,25 @@ def test_token_bank_prefill(flags):
         U.run_bank_case(synth.scaled(w, k=2048, q_len=200, batch=1, kv_len=6000, page_size=4), 0.5)
     U.run_bank_case(synth.scaled(w, dtype="fp32", q_len=300, head_dim=64), 0.5, flags)
     U.run_bank_case(synth.scaled(w, page_size=6, q_len=300), 0.5, flags)   # not a power of two
+
+
+def test_pages_read_map_accumulates():
+    # the library only ever stores 1 into the map: bytes set before the call stay set, two calls leave the union
+    w = synth.Workload("bank_acc", 2, 4, 2, 128, 1, 4000, 128, 1, 2, "bf16", rho=0.9, ragged=(2000, 4000), page_size=16,
+                       integer=True, seed=124)
+    x = synth.make_inputs(w, device="cuda", threads=4)
+    kw = dict(kv_lens=x["kv_lens"], page_table=x["page_table"])
+    a = torch.zeros_like(x["page_table"], dtype=torch.uint8)
+    b = torch.zeros_like(a)
+    idx = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, touched=a, **kw)
+    hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, touched=b, n_window=5, **kw)
+    both = a.clone()
+    both[0, -1] = 1                                   # a byte of the caller's (beyond the first sequence's pages)
+    hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, touched=both, n_window=5, **kw)
+    torch.cuda.synchronize()
+    want = a | b
+    want[0, -1] = 1
+    assert torch.equal(both, want) and bool(a.any()) and bool(b.any()) and int(a.max()) == 1
 
 
 def test_token_bank_in_host_memory():
