@@ -171,27 +171,6 @@ size_t hip_workspace_bytes(const hip_problem *p);
 /* Static, human-readable text for a return code. */
 const char *hip_strerror(int code);
 
-/* Test aid, not part of the method: fills the LDS of every compute unit with `pattern` (one
- * kernel on `stream`), so that a kernel that wrongly reads LDS it never wrote sees that value
- * instead of whatever an earlier kernel left there.  The GPU tests call it before every call. */
-int hip_attn_poison_lds(uint32_t pattern, void *stream);
-
-/* Measurement aids, not part of the method: the ceilings this GPU sustains, for quoting roofline
- * fractions against measured figures next to the published ones.
- *   hip_attn_probe_copy : one kernel copies `bytes` (a multiple of 16) from device `src` to device `dst`
- *                         (both 16-byte aligned, not overlapping): HBM traffic = 2 * bytes.
- *   hip_attn_probe_read : one kernel reads `bytes` (a multiple of 16) from device `src` (16-byte aligned) and
- *                         writes the XOR of the words each lane saw to device `out`
- *                         [HIP_ATTN_PROBE_READ_WORDS uint32]: HBM traffic = bytes (+ 8 MiB written).
- *   hip_attn_probe_mfma : `workgroups` workgroups of 4 waves; every wave issues iters * 4 independent
- *                         32x32x16 bf16 matrix instructions (2*32*32*16 flop each) on register operands and
- *                         writes one float per lane to device `out` [workgroups * 256].
- * The caller times them with events on `stream`. */
-int hip_attn_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
-#define HIP_ATTN_PROBE_READ_WORDS (256 * 32 * 256)
-int hip_attn_probe_read(uint32_t *out, const void *src, size_t bytes, void *stream);
-int hip_attn_probe_mfma(float *out, int32_t workgroups, int32_t iters, void *stream);
-
 /* Library version, major*100 + minor. */
 int hip_attn_version(void);
 

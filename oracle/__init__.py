@@ -214,3 +214,18 @@ def sparse_attn(p: Problem, Q, K, V, indices, sm_scale: float = 0.0) -> np.ndarr
     nqb = p.n_query_blocks
     O = Ou.reshape(p.batch, p.n_q_heads, nqb * p.bq, p.head_dim)[:, :, :p.q_len, :]
     return np.ascontiguousarray(O)
+
+
+def problem_for(w, x, n_threads: int = 8, **options) -> Problem:
+    """The Problem of a seeded workload description `w` (fields batch, n_q_heads, ..., page_size) and its
+    generated inputs `x` (a dict with "kv_lens" and "page_table", tensors or None); `options` are Problem's
+    optional fields (n_sink, n_window, b_sq, b_sk, rep_pos, top_r)."""
+    lens = x["kv_lens"].cpu().numpy() if x["kv_lens"] is not None else None
+    table = x["page_table"].cpu().numpy() if x["page_table"] is not None else None
+    return Problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
+                   kv_lens=lens, page_table=table, page_size=w.page_size, n_threads=n_threads, **options)
+
+
+def host_arrays(x) -> dict:
+    """Q, K, V of generated inputs as float32 numpy arrays (the dtype-rounded values, exactly)."""
+    return {n: x[n].float().cpu().numpy() for n in ("Q", "K", "V")}

@@ -16,12 +16,12 @@
  * Inputs are float arrays that already hold the dtype-rounded values (a bf16
  * value is exactly representable as a float); every sum is taken in double.
  *
- * Pins (tests/test_oracle_*.py): dense causal attention when k >= T; a literal
- * fixed-array transcription of Alg. 1 enumerated on tiny T; monotone-score
+ * Pins (tests/test_oracle_*.py): dense causal attention when k >= T; a fixed-depth
+ * search over explicit sets of key blocks enumerated on tiny T; monotone-score
  * closed form; kb = 1 greedy binary search; the T=4k,k=512,bq=32,bk=2 structure
  * the paper prints (initial group of 8 blocks, 3 effective rounds); invariants.
  * The numeric VALUES of indices on random data have no printed example in the
- * paper: for those the oracle is pinned only by the brute-force transcription
+ * paper: for those the oracle is pinned only by the brute-force set search
  * and the stated readings ("parity unpinned" by a paper-printed value).
  */
 #include <math.h>

@@ -4,8 +4,7 @@
 (hand-written HIP kernels for gfx950); see include/hipattn.h for the contract.
 """
 from .binding import (BF16, F32, FORCE_GENERIC, SENTINEL, HipAttnError, HipProblem, hip_mask_estimate,
-                      hip_sparse_attn, load, make_problem, poison_lds, probe_copy, probe_mfma,
-                      probe_read, PROBE_READ_WORDS)
+                      hip_sparse_attn, load, make_problem)
 
 __all__ = ["hip_mask_estimate", "hip_sparse_attn", "make_problem", "load", "HipProblem", "HipAttnError",
-           "SENTINEL", "F32", "BF16", "FORCE_GENERIC", "poison_lds", "probe_copy", "probe_mfma", "probe_read", "PROBE_READ_WORDS"]
+           "SENTINEL", "F32", "BF16", "FORCE_GENERIC"]

@@ -18,8 +18,7 @@ SENTINEL = 2**31 - 1
 F32, BF16 = 0, 1
 FORCE_GENERIC = 1
 
-EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version",
-           "hip_attn_poison_lds", "hip_attn_probe_copy", "hip_attn_probe_read", "hip_attn_probe_mfma")
+EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
 
 
 class HipProblem(ctypes.Structure):
@@ -61,8 +60,6 @@ def load() -> ctypes.CDLL:
         lib.hip_strerror.restype = ctypes.c_char_p
         lib.hip_strerror.argtypes = [ctypes.c_int]
         lib.hip_attn_version.restype = ctypes.c_int
-        lib.hip_attn_poison_lds.restype = ctypes.c_int
-        lib.hip_attn_poison_lds.argtypes = [ctypes.c_uint32, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -135,48 +132,6 @@ def _token_bank(p: HipProblem, K, page_table, k_backing, v_backing, touched) -> 
 
 def _stream(t: torch.Tensor) -> int:
     return torch.cuda.current_stream(t.device).cuda_stream
-
-
-def poison_lds(pattern: int = 0xAAAAAAAA) -> None:
-    """Test aid: overwrite the LDS of every compute unit (see include/hipattn.h)."""
-    rc = load().hip_attn_poison_lds(pattern, torch.cuda.current_stream().cuda_stream)
-    if rc != 0:
-        raise HipAttnError(rc)
-
-
-def probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
-    """Measurement aid: one copy kernel src -> dst (see include/hipattn.h)."""
-    _need_gpu(dst, src)
-    n = src.numel() * src.element_size()
-    assert dst.numel() * dst.element_size() == n and dst.is_contiguous() and src.is_contiguous()
-    rc = load().hip_attn_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
-                                    ctypes.c_size_t(n), ctypes.c_void_p(_stream(src)))
-    if rc != 0:
-        raise HipAttnError(rc)
-
-
-PROBE_READ_WORDS = 256 * 32 * 256
-
-
-def probe_read(out: torch.Tensor, src: torch.Tensor) -> None:
-    """Measurement aid: one read-only sweep of src; out (int32 [PROBE_READ_WORDS]) receives per-lane XORs."""
-    _need_gpu(out, src)
-    assert out.dtype == torch.int32 and out.is_contiguous() and out.numel() >= PROBE_READ_WORDS and src.is_contiguous()
-    rc = load().hip_attn_probe_read(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(src.data_ptr()),
-                                    ctypes.c_size_t(src.numel() * src.element_size()), ctypes.c_void_p(_stream(src)))
-    if rc != 0:
-        raise HipAttnError(rc)
-
-
-def probe_mfma(out: torch.Tensor, workgroups: int, iters: int) -> float:
-    """Measurement aid: back-to-back bf16 MFMAs; returns the flops the launch performs."""
-    _need_gpu(out)
-    assert out.dtype == torch.float32 and out.is_contiguous() and out.numel() >= workgroups * 256
-    rc = load().hip_attn_probe_mfma(ctypes.c_void_p(out.data_ptr()), ctypes.c_int32(workgroups), ctypes.c_int32(iters),
-                                    ctypes.c_void_p(_stream(out)))
-    if rc != 0:
-        raise HipAttnError(rc)
-    return workgroups * 4 * iters * 4 * 2.0 * 32 * 32 * 16
 
 
 def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,

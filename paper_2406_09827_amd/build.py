@@ -9,6 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhipattn.so")
+CSRC_AUX = os.path.join(HERE, "csrc_aux")
+LIB_AUX = os.path.join(HERE, "libhipattn_aux.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -fno-honor-nans: max/min compile to single instructions (no NaN quieting); infinities are
@@ -46,6 +48,16 @@ def build_lib(jobs: int = 8) -> str:
     return LIB
 
 
+def build_aux() -> str:
+    """The test and measurement aids (include/hipattn_aux.h): a library of their own, so that the product
+    library exports the method's calls only."""
+    cmd = [HIPCC, *FLAGS, "-shared", os.path.join(CSRC_AUX, "probes.hip"), "-o", LIB_AUX]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on probes.hip:\n{r.stdout}\n{r.stderr}")
+    return LIB_AUX
+
+
 def build_c_example() -> str:
     """Compile the plain-C caller of the ABI (tests/c_abi/c_abi_smoke.c) with gcc against the built
     library; the GPU tests run the binary.  Also proves that include/hipattn.h is valid C."""
@@ -65,4 +77,5 @@ def build_c_example() -> str:
 
 if __name__ == "__main__":
     print(build_lib())
+    print(build_aux())
     print(build_c_example())

@@ -68,13 +68,6 @@ int prepare(const hip_problem *hp, KParams &kp)
     return HIP_ATTN_OK;
 }
 
-__global__ __launch_bounds__(kThreads) void poison_lds_kernel(uint32_t pattern)
-{
-    extern __shared__ uint32_t lds_words[];
-    volatile uint32_t *w = lds_words;  // volatile: the stores are the whole point
-    for (int i = threadIdx.x; i < 65536 / 4; i += kThreads) w[i] = pattern;
-}
-
 int launch_result(hipError_t e) { return e == hipSuccess ? HIP_ATTN_OK : HIP_ATTN_ELAUNCH - (int)e; }
 
 }  // namespace
@@ -160,34 +153,6 @@ const char *hip_strerror(int code)
         case HIP_ATTN_EWORKSPACE: return "workspace smaller than hip_workspace_bytes()";
         default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
     }
-}
-
-int hip_attn_poison_lds(uint32_t pattern, void *stream)
-{
-    // 2 workgroups of 64 KB fit a compute unit: 8192 workgroups sweep all 256 units many times
-    hipLaunchKernelGGL(poison_lds_kernel, dim3(8192), dim3(kThreads), 65536, static_cast<hipStream_t>(stream), pattern);
-    return launch_result(hipGetLastError());
-}
-
-int hip_attn_probe_copy(void *dst, const void *src, size_t bytes, void *stream)
-{
-    if (!dst || !src) return HIP_ATTN_ENULL;
-    if (!aligned16(dst) || !aligned16(src) || bytes % 16) return HIP_ATTN_EALIGN;
-    return launch_result(launch_probe_copy(dst, src, (int64_t)bytes, static_cast<hipStream_t>(stream)));
-}
-
-int hip_attn_probe_read(uint32_t *out, const void *src, size_t bytes, void *stream)
-{
-    if (!out || !src) return HIP_ATTN_ENULL;
-    if (!aligned16(src) || bytes % 16) return HIP_ATTN_EALIGN;
-    return launch_result(launch_probe_read(out, src, (int64_t)bytes, static_cast<hipStream_t>(stream)));
-}
-
-int hip_attn_probe_mfma(float *out, int32_t workgroups, int32_t iters, void *stream)
-{
-    if (!out) return HIP_ATTN_ENULL;
-    if (workgroups <= 0 || iters <= 0) return HIP_ATTN_ESHAPE;
-    return launch_result(launch_probe_mfma(out, workgroups, iters, static_cast<hipStream_t>(stream)));
 }
 
 int hip_attn_version(void) { return 104; }

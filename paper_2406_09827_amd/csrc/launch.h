@@ -14,10 +14,6 @@ hipError_t launch_mask_decode(const KParams &p, hipStream_t st);
 bool attn_decode_supported(const KParams &p, bool bf16);
 hipError_t launch_attn_decode(const KParams &p, hipStream_t st);
 hipError_t launch_attn_generic(const KParams &p, bool bf16, hipStream_t st);
-hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t st);
-constexpr int kProbeReadGrid = 256 * 32;  // workgroups of the read probe (its output holds one word per lane)
-hipError_t launch_probe_read(uint32_t *out, const void *src, int64_t bytes, hipStream_t st);
-hipError_t launch_probe_mfma(float *out, int workgroups, int iters, hipStream_t st);
 hipError_t launch_topr_mask(const KParams &p, bool bf16, void *dst, hipStream_t st);
 hipError_t launch_touch_attn(const KParams &p, hipStream_t st);
 

@@ -11,19 +11,38 @@ import paper_2406_09827_amd as hipattn
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hipattn.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(hip_[a-z_]+)\s*\(", text)))
 
 
+def _exported(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, capture_output=True, text=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if " T " in line}
+
+
 def test_library_exports_every_declared_symbol():
     lib = hipattn.load()
-    names = _declared_symbols()
+    names = _declared_symbols("hipattn.h")
     assert set(names) >= {"hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror"}
     for n in names:
         assert hasattr(lib, n), n
     assert lib.hip_attn_version() >= 100
+    # the product library exports the declared calls and nothing else that looks like an entry point
+    assert {n for n in _exported(hipattn.binding.LIB_PATH) if n.startswith("hip_")} == set(names)
+
+
+def test_aux_library_exports_every_declared_symbol():
+    from paper_2406_09827_amd import probes
+    lib = probes.load()
+    names = _declared_symbols("hipattn_aux.h")
+    assert set(names) == set(probes.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    # every header of include/ is covered by one of the two tests
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["hipattn.h", "hipattn_aux.h"]
 
 
 def _ok_problem():

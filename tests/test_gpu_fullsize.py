@@ -63,14 +63,19 @@ def _fullsize(w, n_units, seed):
     worst, agree, total = 0.0, 0, 0
     for (b, h, qb) in units:
         hk = h // (w.n_q_heads // w.n_kv_heads)
+        table = None
+        if w.page_size:
+            # the sequence's own pages, in logical order, as a pool of their own
+            n_pages = -(-int(p.kv_lens[b] if p.kv_lens is not None else w.kv_len) // w.page_size)
+            pages = x["page_table"][b, :n_pages].long()
+            table = np.arange(n_pages, dtype=np.int32)[None]
         sub = oracle.Problem(1, 1, 1, w.head_dim, w.q_len, w.kv_len, w.k, w.bq, w.bk,
                              kv_lens=None if p.kv_lens is None else p.kv_lens[b:b + 1],
-                             page_table=None if p.page_table is None else p.page_table[b:b + 1],
-                             page_size=w.page_size)
+                             page_table=table, page_size=w.page_size)
         Q = x["Q"][b:b + 1, h:h + 1].float().cpu().numpy()
         if w.page_size:
-            K = x["K"][:, hk:hk + 1].float().cpu().numpy()
-            V = x["V"][:, hk:hk + 1].float().cpu().numpy()
+            K = x["K"][pages, hk:hk + 1].float().cpu().numpy()
+            V = x["V"][pages, hk:hk + 1].float().cpu().numpy()
         else:
             K = x["K"][b:b + 1, hk:hk + 1].float().cpu().numpy()
             V = x["V"][b:b + 1, hk:hk + 1].float().cpu().numpy()
@@ -107,6 +112,14 @@ def test_c5_ragged_paged_quarter_batch():
     w = synth.scaled(synth.C5, batch=64)
     agr, err = _fullsize(w, 24, seed=5)
     print(f"C5/4: agreement {agr:.6f}, max |dO| {err:.3e}")
+
+
+def test_c5_full_batch():
+    # the ragged, paged decode workload as bench.py launches it: 256 sequences = 8192 (sequence, head) problems
+    # (the shallow-stage, one-problem-per-wave decode kernels; ~18 GiB pools, 64-bit page offsets); only the
+    # sampled sequences' rows go to the host
+    agr, err = _fullsize(synth.C5, 32, seed=9)
+    print(f"C5 full batch: agreement {agr:.6f}, max |dO| {err:.3e}")
 
 
 def test_c2_shape_at_128k_and_256k():

@@ -2,7 +2,7 @@
 
 Each test names the passage of the paper, or the mathematical fact, it checks:
   P1  k >= T  =>  every visible block selected, sparse attention == dense causal softmax (Eq. 1-3)
-  P2  oracle == literal fixed-array transcription of Alg. 1 on tiny inputs (brute force)
+  P2  oracle == the fixed-depth search over explicit block sets (tests/alg1_sets.py) on tiny inputs (brute force)
   P3  T=4k, k=512, bq=32, bk=2: initial group of 8 blocks, final mask after 3 iterations
       (appendix "Hierarchical Attention Mask Pruning Visualization"), <= (k/bk) * log T key
       blocks scored per round budget (Sec. 3.3 first sentence)
@@ -14,7 +14,7 @@ Each test names the passage of the paper, or the mathematical fact, it checks:
   P9  sink + sliding window (appendix "Block Sparse Flash Attention"): a window covering everything is dense
       causal attention; selected blocks + sink + window == dense attention with the union as additive mask
   P10 token bank (Sec. 3.3): results do not depend on which pages are resident; the map of pages read equals
-      the pages of the blocks the literal transcription scores / of the keys in the rows' key sets
+      the pages of the blocks the set-based restatement scores / of the keys in the rows' key sets
 """
 import math
 import os
@@ -25,7 +25,7 @@ import torch
 
 import oracle
 from oracle import Problem, SENTINEL
-from tests.alg1_literal import literal_mask_unit
+from tests.alg1_sets import set_search_mask_unit
 from paper_2406_09827_amd import synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -65,8 +65,8 @@ def test_p1_dense_equivalence(T, bq, bk, d, hq, hkv):
 
 
 # ----------------------------------------------------------------------------- P2
-def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, scored=None):
-    """Scores for the literal transcription are formed here from exact rationals of the
+def _set_search_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, scored=None):
+    """Scores for the set-based restatement are formed here from exact rationals of the
     (integer-valued) inputs or from float64 dot products.  `scored` (a list) collects the 1-based
     blocks whose score is asked for."""
     g = p.n_q_heads // p.n_kv_heads
@@ -95,12 +95,12 @@ def _literal_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, score
                 best = max(best, s)
         return best
 
-    blocks = literal_mask_unit(score, Tb, p.kb, rep_pos)
+    blocks = set_search_mask_unit(score, Tb, p.kb, rep_pos)
     return [(r1 - 1) * p.bk for r1 in blocks]
 
 
 @pytest.mark.parametrize("integer", [True, False])
-def test_p2_literal_alg1_bruteforce(integer):
+def test_p2_set_search_bruteforce(integer):
     rng = np.random.default_rng(5 if integer else 6)
     d = 4 if integer else 8      # few channels + 9 values => very many exact ties
     n_checked = 0
@@ -118,13 +118,13 @@ def test_p2_literal_alg1_bruteforce(integer):
                     nqb = p.n_query_blocks
                     for qb in sorted({0, nqb // 3, nqb // 2, nqb - 2, nqb - 1} & set(range(nqb))):
                         for h in (0, 1):
-                            want = _literal_indices(p, Q, K, 0, h, qb, T)
+                            want = _set_search_indices(p, Q, K, 0, h, qb, T)
                             assert _valid(idx[0, h, qb]) == want, (bk, bq, kb, T, qb, h)
                             n_checked += 1
     assert n_checked > 3000
 
 
-def test_p2_literal_alg1_decode_lengths():
+def test_p2_set_search_decode_lengths():
     rng = np.random.default_rng(8)
     for bk in (1, 2, 4):
         for kb in (1, 2, 5, 8):
@@ -135,12 +135,12 @@ def test_p2_literal_alg1_decode_lengths():
             K = _rand((B, 1, T, d), rng, True)
             idx = oracle.mask_estimate(p, Q, K)
             for b in range(B):
-                assert _valid(idx[b, 0, 0]) == _literal_indices(p, Q, K, b, 0, 0, int(lens[b]))
+                assert _valid(idx[b, 0, 0]) == _set_search_indices(p, Q, K, b, 0, 0, int(lens[b]))
 
 
 def test_p2_gqa_head_mapping():
     """Query head h reads KV head h // (Hq/Hkv) (grouped-query convention, as in
-    torch's repeat_interleave of KV heads); checked against the literal transcription."""
+    torch's repeat_interleave of KV heads); checked against the set-based restatement."""
     rng = np.random.default_rng(12)
     B, hq, hkv, d, T, bq, bk, kb = 2, 4, 2, 8, 96, 4, 2, 6
     p = Problem(B, hq, hkv, d, T, T, kb * bk, bq, bk)
@@ -150,7 +150,7 @@ def test_p2_gqa_head_mapping():
     for b in range(B):
         for h in range(hq):
             for qb in (10, 17, p.n_query_blocks - 1):
-                assert _valid(idx[b, h, qb]) == _literal_indices(p, Q, K, b, h, qb, T)
+                assert _valid(idx[b, h, qb]) == _set_search_indices(p, Q, K, b, h, qb, T)
         differ |= not np.array_equal(idx[b, 0], idx[b, 2])
     assert differ
 
@@ -158,7 +158,7 @@ def test_p2_gqa_head_mapping():
 @pytest.mark.parametrize("integer", [True, False])
 def test_p2_scoring_variants(integer):
     """Sampling strides inside the block score (Sec. 3.2) and the representative position, against the
-    literal transcription with the same options; and a case built so that each option changes the result."""
+    set-based restatement with the same options; and a case built so that each option changes the result."""
     rng = np.random.default_rng(31 if integer else 32)
     d = 4 if integer else 8
     n = 0
@@ -170,7 +170,7 @@ def test_p2_scoring_variants(integer):
                     Q, K = _rand((1, 1, T, d), rng, integer), _rand((1, 1, T, d), rng, integer)
                     idx = oracle.mask_estimate(p, Q, K)
                     for qb in sorted({0, p.n_query_blocks // 2, p.n_query_blocks - 1}):
-                        want = _literal_indices(p, Q, K, 0, 0, qb, T, b_sq, b_sk, rep_pos)
+                        want = _set_search_indices(p, Q, K, 0, 0, qb, T, b_sq, b_sk, rep_pos)
                         assert _valid(idx[0, 0, qb]) == want, (bq, bk, b_sq, b_sk, rep_pos, kb, T, qb)
                         n += 1
     assert n > 500
@@ -205,7 +205,7 @@ def _mask_channels(Q, r):
 @pytest.mark.parametrize("integer", [True, False])
 def test_p2_top_r_channels(integer):
     """Top-r approximation of the scores (appendix "Top-r Approximation"): identical to running the
-    literal transcription on queries whose other channels are zeroed; r = d (or 0) is the plain method;
+    set-based restatement on queries whose other channels are zeroed; r = d (or 0) is the plain method;
     and a case built so that r changes the selected block."""
     rng = np.random.default_rng(41 if integer else 42)
     d, n = 8, 0
@@ -219,7 +219,7 @@ def test_p2_top_r_channels(integer):
                     Qm = _mask_channels(Q, r)
                     for qb in sorted({0, p.n_query_blocks // 2, p.n_query_blocks - 1}):
                         for h in (0, 1):
-                            assert _valid(idx[0, h, qb]) == _literal_indices(p, Qm, K, 0, h, qb, T), (bq, bk, r, kb, T, qb)
+                            assert _valid(idx[0, h, qb]) == _set_search_indices(p, Qm, K, 0, h, qb, T), (bq, bk, r, kb, T, qb)
                             n += 1
     assert n > 500
     p0 = Problem(1, 2, 1, d, 130, 130, 16, 4, 2)
@@ -527,7 +527,7 @@ def test_p10_results_do_not_depend_on_residency(resident_frac, q_len):
 
 @pytest.mark.parametrize("q_len,rep_pos,b_sk", [(1, 0, 1), (23, 0, 1), (23, 2, 2), (1, 1, 1)])
 def test_p10_pages_read_by_mask_estimation(q_len, rep_pos, b_sk):
-    # the map must hold exactly the pages of the representative blocks that the literal transcription scores
+    # the map must hold exactly the pages of the representative blocks that the set-based restatement scores
     # (units whose visible blocks all fit are dense and read nothing)
     w, x, xb = _bank_case(0.5, q_len, 32)
     Q, lens = _np(x, "Q", "kv_lens")
@@ -548,7 +548,7 @@ def test_p10_pages_read_by_mask_estimation(q_len, rep_pos, b_sk):
         if L <= 0 or -(-L // w.bk) <= w.kb:
             continue
         scored = []
-        _literal_indices(pc, Q, Kc, b, h, qb, kv_len, 1, b_sk, rep_pos, scored)
+        _set_search_indices(pc, Q, Kc, b, h, qb, kv_len, 1, b_sk, rep_pos, scored)
         for r1 in scored:
             want[b, (r1 - 1) * w.bk // w.page_size] = 1
     assert want.any() and np.array_equal(touched, want)
@@ -584,3 +584,66 @@ def test_p10_pages_read_by_sparse_attention(q_len, n_sink, n_window):
                     if 0 <= t <= pos and t < lens[b]:
                         want[b, t // w.page_size] = 1
     assert want.any() and np.array_equal(touched, want)
+
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle built with -fsanitize=address,undefined runs a set of problems that walks every code path (prefill and
+    decode, ragged, paged with a token bank and the map of pages read, every scoring option, sink and window) without
+    a report, and returns what the regular build returns."""
+    import subprocess
+    import sys
+    import textwrap
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = tmp_path / "libhip_oracle_san.so"
+    subprocess.run(["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=all", "-o", str(lib), os.path.join(root, "oracle", "hip_oracle.c"), "-lm"], check=True)
+    asan = subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True, text=True).stdout.strip()
+    script = textwrap.dedent(f"""
+        import ctypes, sys
+        import numpy as np
+        sys.path.insert(0, {root!r})
+        import oracle
+        rng = np.random.default_rng(5)
+        def run():
+            res = []
+            for (T, q_len, bq, bk, kb, page, opts) in [
+                    (97, 97, 4, 2, 8, 0, {{}}), (64, 64, 16, 1, 3, 0, dict(b_sq=2, rep_pos=1)),
+                    (130, 1, 1, 2, 16, 4, dict(rep_pos=2, b_sk=2, n_sink=3, n_window=5)),
+                    (75, 20, 8, 4, 4, 8, dict(top_r=3, n_window=7)), (33, 33, 32, 2, 64, 0, {{}})]:
+                B, Hq, Hkv, d = 2, 4, 2, 8
+                lens = rng.integers(max(q_len, T // 2), T + 1, size=B).astype(np.int32)
+                Q = rng.integers(-4, 5, size=(B, Hq, q_len, d)).astype(np.float32) / 8
+                if page:
+                    mp = -(-T // page)
+                    n_pool = B * mp
+                    table = rng.permutation(n_pool).astype(np.int32).reshape(B, mp)
+                    miss = rng.random(table.shape) < 0.5
+                    K = rng.integers(-4, 5, size=(n_pool, Hkv, page, d)).astype(np.float32) / 8
+                    V = rng.integers(-4, 5, size=(n_pool, Hkv, page, d)).astype(np.float32) / 8
+                    table = np.where(miss, -table - 1, table).astype(np.int32)
+                    touched = np.zeros(table.shape, np.uint8)
+                    p = oracle.Problem(B, Hq, Hkv, d, q_len, T, kb * bk, bq, bk, kv_lens=lens, page_table=table, page_size=page,
+                                       n_threads=2, k_backing=K, v_backing=V, touched=touched, **opts)
+                else:
+                    K = rng.integers(-4, 5, size=(B, Hkv, T, d)).astype(np.float32) / 8
+                    V = rng.integers(-4, 5, size=(B, Hkv, T, d)).astype(np.float32) / 8
+                    p = oracle.Problem(B, Hq, Hkv, d, q_len, T, kb * bk, bq, bk, kv_lens=lens, n_threads=2, **opts)
+                idx = oracle.mask_estimate(p, Q, K)
+                out = oracle.sparse_attn(p, Q, K, V, idx, 0.3)
+                res.append((idx.copy(), out.copy()))
+            return res
+        plain = run()
+        oracle._lib = None
+        oracle.build = lambda force=False: {str(lib)!r}
+        rng = np.random.default_rng(5)
+        san = run()
+        for (i0, o0), (i1, o1) in zip(plain, san):
+            assert np.array_equal(i0, i1) and np.array_equal(o0, o1)
+        print("sanitized oracle agrees on", len(san), "problems")
+    """)
+    # the sanitizer runtime goes first in the preload list; whatever the environment already preloads stays
+    preload = ":".join(x for x in (asan, os.environ.get("LD_PRELOAD", "")) if x)
+    env = dict(os.environ, LD_PRELOAD=preload, ASAN_OPTIONS="detect_leaks=0:abort_on_error=1", UBSAN_OPTIONS="halt_on_error=1")
+    r = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
+    assert "sanitized oracle agrees on 5 problems" in r.stdout
