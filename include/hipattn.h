@@ -57,6 +57,7 @@ enum {
     HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0; a backing   */
                                /* pool or a touched map without a page table                   */
     HIP_ATTN_EWORKSPACE = -9,  /* workspace_bytes below hip_workspace_bytes()                 */
+    HIP_ATTN_ESCRATCH = -10,   /* hip_mask_estimate_noalloc: hip_workspace_bytes() above the static scratch */
     HIP_ATTN_ELAUNCH = -1000   /* launch failure: code is HIP_ATTN_ELAUNCH - hipError_t       */
 };
 
@@ -167,6 +168,20 @@ int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const vo
 /* Device scratch hip_mask_estimate needs for this problem: one copy of Q when top_r is in use,
  * otherwise 0 (the kernels keep their state in LDS and registers).  hip_sparse_attn needs none. */
 size_t hip_workspace_bytes(const hip_problem *p);
+
+/*
+ * hip_mask_estimate for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and errors as
+ * hip_mask_estimate, except that p->workspace / p->workspace_bytes are ignored: the scratch the top_r option
+ * needs (hip_workspace_bytes(p) bytes) is a static array of HIP_ATTN_STATIC_SCRATCH_BYTES inside the library,
+ * one copy per GPU, held until the process ends.  A problem that needs more returns HIP_ATTN_ESCRATCH before any
+ * launch.  The call allocates and frees nothing.  Every call on a GPU shares that GPU's array (it keeps the last
+ * call's contents; the call overwrites what it reads): calls that overlap in time on one GPU - different streams,
+ * or different host threads - race on it and must be serialised by the caller.
+ */
+#define HIP_ATTN_STATIC_SCRATCH_BYTES (8u << 20)
+int hip_mask_estimate_noalloc(const hip_problem *p, const void *Q, const void *K, int32_t *indices,
+                              void *stream);
 
 /* Static, human-readable text for a return code. */
 const char *hip_strerror(int code);

@@ -18,7 +18,7 @@ SENTINEL = 2**31 - 1
 F32, BF16 = 0, 1
 FORCE_GENERIC = 1
 
-EXPORTS = ("hip_mask_estimate", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
+EXPORTS = ("hip_mask_estimate", "hip_mask_estimate_noalloc", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
 
 
 class HipProblem(ctypes.Structure):
@@ -52,6 +52,8 @@ def load() -> ctypes.CDLL:
         lib.hip_mask_estimate.restype = ctypes.c_int
         lib.hip_mask_estimate.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_void_p]
+        lib.hip_mask_estimate_noalloc.restype = ctypes.c_int
+        lib.hip_mask_estimate_noalloc.argtypes = lib.hip_mask_estimate.argtypes
         lib.hip_sparse_attn.restype = ctypes.c_int
         lib.hip_sparse_attn.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -156,6 +158,25 @@ def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=N
     assert indices.dtype == torch.int32 and indices.is_contiguous()
     assert indices.numel() == p.batch * p.n_q_heads * nqb * (k // bk)
     rc = lib.hip_mask_estimate(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), indices.data_ptr(), _stream(Q))
+    if rc != 0:
+        raise HipAttnError(rc)
+    return indices
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def hip_mask_estimate_noalloc(Q, K, k: int, bq: int, bk: int, indices: torch.Tensor, kv_lens=None, page_table=None,
+                              max_kv_len=None, flags: int = 0, b_sq: int = 1, b_sk: int = 1, rep_pos: int = 0,
+                              top_r: int = 0) -> torch.Tensor:
+    """hip_mask_estimate without any allocation: the caller passes `indices`, and the scratch of the top_r option is
+    the library's static array (see include/hipattn.h)."""
+    _need_gpu(Q, K, kv_lens, page_table, indices)
+    p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
+    p.b_sq, p.b_sk, p.rep_pos, p.top_r = b_sq, b_sk, rep_pos, top_r
+    assert indices.dtype == torch.int32 and indices.is_contiguous()
+    assert indices.numel() == p.batch * p.n_q_heads * ((p.q_len + bq - 1) // bq) * (k // bk)
+    rc = load().hip_mask_estimate_noalloc(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), indices.data_ptr(), _stream(Q))
     if rc != 0:
         raise HipAttnError(rc)
     return indices

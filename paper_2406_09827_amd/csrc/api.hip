@@ -3,9 +3,36 @@
 #include "common.h"
 #include "launch.h"
 
+#include <mutex>
+
 using namespace hipattn;
 
+// Scratch of hip_mask_estimate_noalloc: lives in the code object, one copy per GPU the library is loaded on,
+// held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[HIP_ATTN_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, looked up once per GPU
+std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch` (nullptr + error code on failure).
+void *static_scratch(hipError_t &err)
+{
+    int dev = -1;
+    err = hipGetDevice(&dev);
+    if (err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) { err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));  // with device `dev` current: its own copy
+        if (err != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -74,7 +101,9 @@ int launch_result(hipError_t e) { return e == hipSuccess ? HIP_ATTN_OK : HIP_ATT
 
 extern "C" {
 
-int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream)
+// Both mask-estimation entry points: `own_scratch` = use the library's static scratch instead of p->workspace.
+static int mask_estimate_impl(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream,
+                              bool own_scratch)
 {
     KParams kp;
     int rc = prepare(p, kp);
@@ -89,20 +118,38 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     const bool bf16 = p->dtype == HIP_ATTN_BF16;
     const bool generic = p->flags & HIP_ATTN_FORCE_GENERIC;
     if (kp.top_r > 0) {
-        // top-r scores: a copy of Q with the unused channels of every row zeroed goes to the workspace,
+        // top-r scores: a copy of Q with the unused channels of every row zeroed goes to the scratch,
         // and the kernels below read that copy (dense layout)
-        if (!p->workspace) return HIP_ATTN_ENULL;
-        if (!aligned16(p->workspace)) return HIP_ATTN_EALIGN;
-        if (p->workspace_bytes < hip_workspace_bytes(p)) return HIP_ATTN_EWORKSPACE;
-        hipError_t e = launch_topr_mask(kp, bf16, p->workspace, st);
+        void *ws = p->workspace;
+        if (own_scratch) {
+            if (hip_workspace_bytes(p) > HIP_ATTN_STATIC_SCRATCH_BYTES) return HIP_ATTN_ESCRATCH;
+            hipError_t e;
+            ws = static_scratch(e);
+            if (!ws) return launch_result(e);
+        } else {
+            if (!ws) return HIP_ATTN_ENULL;
+            if (!aligned16(ws)) return HIP_ATTN_EALIGN;
+            if (p->workspace_bytes < hip_workspace_bytes(p)) return HIP_ATTN_EWORKSPACE;
+        }
+        hipError_t e = launch_topr_mask(kp, bf16, ws, st);
         if (e != hipSuccess) return launch_result(e);
-        kp.Q = p->workspace;
+        kp.Q = ws;
         kp.qs_r = kp.d; kp.qs_h = (int64_t)kp.q_len * kp.d; kp.qs_b = kp.qs_h * kp.hq;
         kp.top_r = 0;
     }
     if (!generic && mask_mfma_supported(kp, bf16)) return launch_result(launch_mask_mfma(kp, st));
     if (!generic && mask_decode_supported(kp, bf16)) return launch_result(launch_mask_decode(kp, st));
     return launch_result(launch_mask_generic(kp, bf16, st));
+}
+
+int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream)
+{
+    return mask_estimate_impl(p, Q, K, indices, stream, false);
+}
+
+int hip_mask_estimate_noalloc(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream)
+{
+    return mask_estimate_impl(p, Q, K, indices, stream, true);
 }
 
 int hip_sparse_attn(const hip_problem *p, const void *Q, const void *K, const void *V, const int32_t *indices,
@@ -151,10 +198,11 @@ const char *hip_strerror(int code)
         case HIP_ATTN_EALIGN: return "pointer or stride not 16-byte aligned";
         case HIP_ATTN_EPAGE: return "invalid page table description (or a backing pool / touched map without a page table)";
         case HIP_ATTN_EWORKSPACE: return "workspace smaller than hip_workspace_bytes()";
+        case HIP_ATTN_ESCRATCH: return "the problem needs more scratch than the library's static HIP_ATTN_STATIC_SCRATCH_BYTES";
         default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
     }
 }
 
-int hip_attn_version(void) { return 104; }
+int hip_attn_version(void) { return 105; }
 
 }  // extern "C"
