@@ -43,6 +43,7 @@ class _Problem(ctypes.Structure):
         ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32),
         ("top_r", ctypes.c_int32),
         ("k_backing", ctypes.c_void_p), ("v_backing", ctypes.c_void_p), ("touched", ctypes.c_void_p),
+        ("ens_sample", ctypes.c_int32), ("ens_seed", ctypes.c_uint32), ("ens_r", ctypes.c_float),
     ]
 
 
@@ -66,6 +67,9 @@ def lib():
         _lib.oracle_hip_mask_estimate_units.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        _lib.oracle_hip_vote.restype = ctypes.c_int
+        _lib.oracle_hip_vote.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
     return _lib
 
 
@@ -96,6 +100,11 @@ class Problem:
     k_backing: Optional[np.ndarray] = None
     v_backing: Optional[np.ndarray] = None
     touched: Optional[np.ndarray] = None
+    # ensemble sample (appendix "Ensemble Hierarchical Top-k Approximation"): 0 = the plain mask; e > 0 adds
+    # ens_r * u, u a counter-based uniform on [-1, 1), to the scores of the middle round
+    ens_sample: int = 0
+    ens_seed: int = 0
+    ens_r: float = 0.0
 
     @property
     def kb(self) -> int:
@@ -110,6 +119,7 @@ class Problem:
         p = _Problem(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.q_len,
                      self.max_kv_len, self.k, self.bq, self.bk, None, None, 0, 0, self.n_threads,
                      self.n_sink, self.n_window, self.b_sq, self.b_sk, self.rep_pos, self.top_r)
+        p.ens_sample, p.ens_seed, p.ens_r = self.ens_sample, self.ens_seed & 0xffffffff, self.ens_r
         if self.kv_lens is not None:
             a = np.ascontiguousarray(self.kv_lens, dtype=np.int32)
             assert a.shape == (self.batch,)
@@ -214,6 +224,20 @@ def sparse_attn(p: Problem, Q, K, V, indices, sm_scale: float = 0.0) -> np.ndarr
     nqb = p.n_query_blocks
     O = Ou.reshape(p.batch, p.n_q_heads, nqb * p.bq, p.head_dim)[:, :, :p.q_len, :]
     return np.ascontiguousarray(O)
+
+
+def vote(samples, theta_vote: int, tau: int) -> np.ndarray:
+    """Ensemble vote: samples [n_e, ..., kb] index sets -> [..., kb if tau else n_e * kb] (see hip_oracle.c)."""
+    samples = np.ascontiguousarray(samples, dtype=np.int32)
+    n_e, kb = samples.shape[0], samples.shape[-1]
+    lead = samples.shape[1:-1]
+    n_units = int(np.prod(lead)) if lead else 1
+    width = kb if tau else n_e * kb
+    out = np.empty((n_units, width), dtype=np.int32)
+    rc = lib().oracle_hip_vote(samples.ctypes.data, n_e, n_units, kb, int(theta_vote), int(tau), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle rejected the vote description")
+    return out.reshape(*lead, width)
 
 
 def problem_for(w, x, n_threads: int = 8, **options) -> Problem:

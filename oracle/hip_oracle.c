@@ -56,6 +56,11 @@ typedef struct {
      * NULL) receives 1 for every logical page of which a call reads a key row (other bytes are left alone). */
     const float *k_backing, *v_backing;
     uint8_t *touched;
+    /* Ensemble sample (appendix "Ensemble Hierarchical Top-k Approximation"): sample 0 is the plain mask; a
+     * sample e > 0 has a pseudo-random term of size ens_r added to the branch scores of its middle round. */
+    int32_t ens_sample;
+    uint32_t ens_seed;
+    float ens_r;
 } oracle_problem;
 
 /* Statistics of one mask-estimation unit, used by the structural pins. */
@@ -91,6 +96,38 @@ static const float *kv_row(const kv_view *v, int64_t t)
 static int64_t rnd_div(int64_t a, int64_t b) { return (2 * a + b) / (2 * b); }
 
 /* ------------------------------------------------------------------------ */
+/* randomness of an ensemble sample                                          */
+/* ------------------------------------------------------------------------ */
+
+/* The paper's ensemble draws several masks "by adding randomness r_e to the branch direction" of a middle
+ * iteration and says no more.  Reading taken here: in round floor(R/2) of the R = ceil(log2(ceil(Tb/kb)))
+ * rounds of a query block (rounds counted from 0), the score that the top-k selection compares is
+ * score + r_e * u with u uniform on [-1, 1); the other rounds, and sample 0, are untouched.  So that a GPU
+ * implementation can draw the SAME u without exchanging random numbers, u is a counter-based value: the
+ * 32-bit finalizer of MurmurHash3 absorbs seed, sample, sequence, head, query block and the representative
+ * key block of the branch one after the other, and the top 24 bits of the result, read as an integer n,
+ * give u = (n - 2^23) / 2^23 (exact in single precision).  The perturbed score is formed in single
+ * precision, product first, then sum (each rounded once), which is the precision the decision is taken in. */
+static uint32_t ens_fmix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    return x;
+}
+
+static float ens_uniform(uint32_t seed, int32_t sample, int32_t b, int32_t h, int32_t qb, int64_t rep_block)
+{
+    uint32_t x = ens_fmix32(seed ^ 0x9e3779b9u);
+    x = ens_fmix32(x ^ (uint32_t)sample);
+    x = ens_fmix32(x ^ (uint32_t)b);
+    x = ens_fmix32(x ^ (uint32_t)h);
+    x = ens_fmix32(x ^ (uint32_t)qb);
+    x = ens_fmix32(x ^ (uint32_t)rep_block);
+    return (float)((int32_t)(x >> 8) - (1 << 23)) / 8388608.0f;
+}
+
+typedef struct { int32_t sample; uint32_t seed; float r; int32_t b, h, qb; } ens_ctx;
+
+/* ------------------------------------------------------------------------ */
 /* mask estimation for one (sequence, query head, query block)  -- Alg. 1    */
 /* ------------------------------------------------------------------------ */
 
@@ -102,7 +139,8 @@ static int64_t rnd_div(int64_t a, int64_t b) { return (2 * a + b) / (2 * b); }
  *          then ORACLE_SENTINEL padding
  */
 static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K, int64_t kv_len,
-                      int kb, int bk, int b_sq, int b_sk, int rep_pos, int top_r, int32_t *out, oracle_mask_stats *st)
+                      int kb, int bk, int b_sq, int b_sk, int rep_pos, int top_r, const ens_ctx *ens,
+                      int32_t *out, oracle_mask_stats *st)
 {
     if (b_sq < 1) b_sq = 1;
     if (b_sk < 1) b_sk = 1;
@@ -149,7 +187,12 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
         }
     }
 
-    for (;;) {
+    /* rounds a block of this length runs, whatever its data: the longest initial node halves (rounding up)
+     * until it is one block long */
+    int n_rounds = 0;
+    for (int64_t len = (Tb + kb - 1) / kb; len > 1; len = (len + 1) / 2) ++n_rounds;
+
+    for (int round = 0;; ++round) {
         int any_split = 0;
         for (int j = 0; j < n; ++j) any_split |= (ne[j] - ns[j] > 1);
         if (!any_split) break; /* every branch has length 1 */
@@ -180,6 +223,12 @@ static void mask_unit(const float *q, int n_rows, int64_t pos0, const kv_view *K
                         if (!use || use[(size_t)m * d + c]) dot += (double)qrow[c] * (double)krow[c];
                     if (dot > best) best = dot;
                 }
+            }
+            if (ens && ens->sample > 0 && round == n_rounds / 2) {
+                /* ensemble sample: this round's selection sees score + r_e * u, in single precision */
+                volatile float pert = ens->r * ens_uniform(ens->seed, ens->sample, ens->b, ens->h, ens->qb, r);
+                volatile float moved = (float)best + pert;
+                best = (double)moved;
             }
             sc[b] = best;
             if (st) st->reps_scored++;
@@ -333,7 +382,8 @@ int oracle_hip_mask_estimate_units(const oracle_problem *p, const float *Q, cons
         int64_t pos0 = kv_len - p->q_len + row0;
         kv_view kv = make_view(p, K, p->k_backing, b, h / g);
         const float *q = Q + (((int64_t)b * p->n_q_heads + h) * p->q_len + row0) * d;
-        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, p->top_r, out + u * kb,
+        ens_ctx ens = {p->ens_sample, p->ens_seed, p->ens_r, b, h, qb};
+        mask_unit(q, n_rows, pos0, &kv, kv_len, kb, p->bk, p->b_sq, p->b_sk, p->rep_pos, p->top_r, &ens, out + u * kb,
                   stats ? stats + u : NULL);
     }
     return 0;
@@ -365,6 +415,63 @@ int oracle_hip_sparse_attn_units(const oracle_problem *p, const float *Q, const 
                   p->n_sink > 0 ? p->n_sink : 0, p->n_window > 0 ? p->n_window : 0,
                   O + u * (int64_t)p->bq * d);
     }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* ensemble vote (appendix "Ensemble Hierarchical Top-k Approximation")      */
+/* ------------------------------------------------------------------------ */
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * samples [n_e][n_units][kb]: n_e index sets per query block (entries < 0 or == ORACLE_SENTINEL: no block;
+ * a set holds a position at most once).  A position's votes = the number of sets that hold it.  Kept: the
+ * positions with votes >= theta_vote (theta_vote = 1: union, = n_e: intersection).  tau = 1: at most kb of
+ * them, those with more votes first, the lower position among equal votes.  out [n_units][width], width =
+ * kb if tau else n_e * kb: the kept positions ascending, then ORACLE_SENTINEL padding.
+ */
+int oracle_hip_vote(const int32_t *samples, int32_t n_e, int64_t n_units, int32_t kb, int32_t theta_vote,
+                    int32_t tau, int32_t *out)
+{
+    if (!samples || !out || n_e <= 0 || kb <= 0 || n_units < 0 || theta_vote < 1) return -1;
+    const int64_t width = tau ? kb : (int64_t)n_e * kb;
+    const size_t cap = (size_t)n_e * (size_t)kb;
+    int32_t *all = malloc(sizeof(int32_t) * cap), *pos = malloc(sizeof(int32_t) * cap), *votes = malloc(sizeof(int32_t) * cap);
+    for (int64_t u = 0; u < n_units; ++u) {
+        size_t n = 0;
+        for (int e = 0; e < n_e; ++e)
+            for (int j = 0; j < kb; ++j) {
+                int32_t v = samples[((int64_t)e * n_units + u) * kb + j];
+                if (v >= 0 && v != ORACLE_SENTINEL) all[n++] = v;
+            }
+        qsort(all, n, sizeof(int32_t), cmp_i32);
+        size_t m = 0; /* distinct positions with enough votes */
+        for (size_t i = 0; i < n;) {
+            size_t j = i;
+            while (j < n && all[j] == all[i]) ++j;
+            if ((int64_t)(j - i) >= theta_vote) { pos[m] = all[i]; votes[m] = (int32_t)(j - i); ++m; }
+            i = j;
+        }
+        int32_t *row = out + u * width;
+        int64_t w = 0;
+        for (size_t i = 0; i < m; ++i) {
+            int take = 1;
+            if (tau && m > (size_t)kb) {
+                size_t rank = 0; /* positions that come before this one: more votes, or as many at a lower position */
+                for (size_t j = 0; j < m; ++j)
+                    if (votes[j] > votes[i] || (votes[j] == votes[i] && j < i)) ++rank;
+                take = rank < (size_t)kb;
+            }
+            if (take) row[w++] = pos[i];
+        }
+        for (; w < width; ++w) row[w] = ORACLE_SENTINEL;
+    }
+    free(all); free(pos); free(votes);
     return 0;
 }
 

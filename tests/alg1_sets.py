@@ -43,26 +43,41 @@ def _representative(group, rep_pos: int) -> int:
     return _nearest(Fraction((group[0] + 1) + (group[-1] + 1), 2))
 
 
-def _refine(groups, depth: int, kb: int, score_fn, rep_pos: int):
+def _refine(groups, depth: int, kb: int, score_fn, rep_pos: int, level: int = 0, adjust=None):
     if depth == 0:
         return groups
     parts = [h for g in groups for h in _halves(g)]
     score = [score_fn(_representative(h, rep_pos)) if h else -math.inf for h in parts]
+    if adjust is not None:
+        # what the selection of this level compares (an ensemble sample moves the scores of one level)
+        score = [adjust(level, _representative(h, rep_pos), sc) if h else sc for h, sc in zip(parts, score)]
     # best first; a real group outranks an empty one even when stride sampling left it no admissible
     # (row, key) pair and its score is -inf too; equal scores: the part that comes first (lower position)
     ranked = sorted(range(len(parts)), key=lambda i: (-score[i], not parts[i], i))
     kept = sorted(ranked[:kb])
-    return _refine([parts[i] for i in kept], depth - 1, kb, score_fn, rep_pos)
+    return _refine([parts[i] for i in kept], depth - 1, kb, score_fn, rep_pos, level + 1, adjust)
 
 
-def set_search_mask_unit(score_fn, Tb: int, kb: int, rep_pos: int = 0):
+def levels_that_split(Tb: int, kb: int) -> int:
+    """Levels at which some group can still hold more than one block: the longest initial group halves, rounding
+    up, until it is a single block."""
+    longest = max((len(g) for g in _initial_groups(Tb, kb)), default=0)
+    n = 0
+    while longest > 1:
+        longest = -(-longest // 2)
+        n += 1
+    return n
+
+
+def set_search_mask_unit(score_fn, Tb: int, kb: int, rep_pos: int = 0, adjust=None):
     """score_fn(r) -> score of key block number r, counted from 1 (max over the query block's rows and the block's
-    keys of the admissible dot products; -inf if none).  Returns the sorted block numbers (from 1) selected."""
+    keys of the admissible dot products; -inf if none); adjust(level, r, score) -> the score the selection of that
+    level (0 = first) compares, if given.  Returns the sorted block numbers (from 1) selected."""
     if Tb <= 0:
         return []
     depth = 0
     while 2 ** depth < Tb:
         depth += 1
-    final = _refine(_initial_groups(Tb, kb), depth, kb, score_fn, rep_pos)
+    final = _refine(_initial_groups(Tb, kb), depth, kb, score_fn, rep_pos, 0, adjust)
     assert all(len(g) <= 1 for g in final), "a group still holds several blocks after ceil(log2(Tb)) levels"
     return sorted(g[0] + 1 for g in final if g)

@@ -25,6 +25,8 @@ import torch
 
 import oracle
 from oracle import Problem, SENTINEL
+from dataclasses import replace
+
 from tests.alg1_sets import set_search_mask_unit
 from paper_2406_09827_amd import synth
 
@@ -65,7 +67,7 @@ def test_p1_dense_equivalence(T, bq, bk, d, hq, hkv):
 
 
 # ----------------------------------------------------------------------------- P2
-def _set_search_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, scored=None):
+def _set_search_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, scored=None, adjust_for=None):
     """Scores for the set-based restatement are formed here from exact rationals of the
     (integer-valued) inputs or from float64 dot products.  `scored` (a list) collects the 1-based
     blocks whose score is asked for."""
@@ -95,7 +97,8 @@ def _set_search_indices(p, Q, K, b, h, qb, kv_len, b_sq=1, b_sk=1, rep_pos=0, sc
                 best = max(best, s)
         return best
 
-    blocks = set_search_mask_unit(score, Tb, p.kb, rep_pos)
+    adjust = adjust_for(Tb) if adjust_for is not None else None
+    blocks = set_search_mask_unit(score, Tb, p.kb, rep_pos, adjust)
     return [(r1 - 1) * p.bk for r1 in blocks]
 
 
@@ -586,6 +589,130 @@ def test_p10_pages_read_by_sparse_attention(q_len, n_sink, n_window):
     assert want.any() and np.array_equal(touched, want)
 
 
+# ----------------------------------------------------------------------------- P11: ensemble of masks
+def _fmix32(x):
+    x ^= x >> 16; x = (x * 0x85ebca6b) & 0xffffffff
+    x ^= x >> 13; x = (x * 0xc2b2ae35) & 0xffffffff
+    x ^= x >> 16
+    return x
+
+
+def _ens_uniform(seed, sample, b, h, qb, rep_block):
+    """The counter-based draw of an ensemble sample (an input convention shared by both implementations, stated in
+    oracle/hip_oracle.c): MurmurHash3's 32-bit finalizer absorbs the six numbers; top 24 bits -> [-1, 1)."""
+    x = _fmix32((seed ^ 0x9e3779b9) & 0xffffffff)
+    for v in (sample, b, h, qb, rep_block):
+        x = _fmix32(x ^ (v & 0xffffffff))
+    return np.float32(((x >> 8) - (1 << 23)) / float(1 << 23))
+
+
+def _ens_adjust(p, seed, sample, r_e, b, h, qb):
+    """adjust_for(Tb) for the set search: scores of level floor(R/2) move by r_e * u, in single precision."""
+    from tests.alg1_sets import levels_that_split
+
+    def adjust_for(Tb):
+        target = levels_that_split(Tb, p.kb) // 2
+
+        def adjust(level, r1, score):
+            if sample == 0 or level != target:
+                return score
+            pert = np.float32(r_e) * _ens_uniform(seed, sample, b, h, qb, r1 - 1)
+            return float(np.float32(score) + pert)
+        return adjust
+    return adjust_for
+
+
+@pytest.mark.parametrize("integer", [True, False])
+def test_p11_ensemble_sample_bruteforce(integer):
+    """An ensemble sample against the set search whose middle level compares score + r_e * u; sample 0 and r_e = 0
+    are the plain mask; with r_e large some sample differs from it."""
+    rng = np.random.default_rng(21 if integer else 22)
+    d = 4 if integer else 8
+    n_checked = n_moved = 0
+    for bk, bq, kb in ((1, 1, 1), (2, 2, 3), (1, 4, 4), (2, 1, 8), (4, 4, 2)):
+        for T in (5, 9, 16, 23, 40, 64, 97, 150, 257):
+            for rep_pos in (0, 1, 2):
+                Q = _rand((2, 2, T, d), rng, integer)
+                K = _rand((2, 1, T, d), rng, integer)
+                base = Problem(2, 2, 1, d, T, T, kb * bk, bq, bk, rep_pos=rep_pos)
+                plain = oracle.mask_estimate(base, Q, K)
+                assert np.array_equal(oracle.mask_estimate(replace(base, ens_sample=0, ens_seed=7, ens_r=9.0), Q, K), plain)
+                assert np.array_equal(oracle.mask_estimate(replace(base, ens_sample=3, ens_seed=7, ens_r=0.0), Q, K), plain)
+                for sample, r_e in ((1, 0.37), (2, 5.0), (5, 300.0)):
+                    p = replace(base, ens_sample=sample, ens_seed=1234 + T, ens_r=r_e)
+                    idx = oracle.mask_estimate(p, Q, K)
+                    n_moved += int(not np.array_equal(idx, plain))
+                    nqb = p.n_query_blocks
+                    for qb in sorted({0, nqb // 2, nqb - 1}):
+                        for b, h in ((0, 1), (1, 0)):
+                            want = _set_search_indices(p, Q, K, b, h, qb, T, rep_pos=rep_pos,
+                                                       adjust_for=_ens_adjust(p, p.ens_seed, sample, r_e, b, h, qb))
+                            assert _valid(idx[b, h, qb]) == want, (bk, bq, kb, T, rep_pos, sample, qb, b, h)
+                            n_checked += 1
+    assert n_checked > 1500 and n_moved > 100
+
+
+def test_p11_ensemble_moves_the_middle_round_only():
+    """8 key blocks, kb = 1: three rounds, the middle one (round 1) is the one that an ensemble sample moves.  Block
+    scores are set up so that the plain search ends at block 5 and only a change of the round-1 decision can end
+    in blocks 6 or 7."""
+    # one channel, q = 1: the score of block t is K[t].  Round 0 compares the centres of [0,4) and [4,8): blocks 2
+    # and 6; round 1 (inside [4,8)) the centres of [4,6) and [6,8): blocks 5 and 7; round 2 blocks 4|5 or 6|7.
+    K = np.array([0, 0, 1, 0, 2, 6, 3, 5], dtype=np.float32).reshape(1, 1, 8, 1)
+    Q = np.ones((1, 1, 1, 1), dtype=np.float32)
+    base = Problem(1, 1, 1, 1, 1, 8, 1, 1, 1)
+    assert _valid(oracle.mask_estimate(base, Q, K)[0, 0, 0]) == [5]
+    seen = set()
+    for sample in range(1, 40):
+        u5, u7 = (_ens_uniform(99, sample, 0, 0, 0, r) for r in (5, 7))
+        for r_e in (0.4, 4.0):
+            got = _valid(oracle.mask_estimate(replace(base, ens_sample=sample, ens_seed=99, ens_r=r_e), Q, K)[0, 0, 0])
+            # round 1 compares 6 + r_e u5 with 5 + r_e u7 (ties to the lower position); then 4|5, resp. 6|7 -> 7
+            right = np.float32(5) + np.float32(r_e) * u7 > np.float32(6) + np.float32(r_e) * u5
+            assert got == ([7] if right else [5]), (sample, r_e)
+            seen.add(got[0])
+    assert seen == {5, 7}
+
+
+def _vote_by_counter(samples, theta, tau, kb):
+    from collections import Counter
+    c = Counter(int(v) for row in samples for v in row if 0 <= v != SENTINEL)
+    kept = [v for v, n in c.items() if n >= theta]
+    if tau and len(kept) > kb:
+        kept = sorted(kept, key=lambda v: (-c[v], v))[:kb]
+    return sorted(kept)
+
+
+def test_p11_vote_union_intersection_truncation():
+    S = SENTINEL
+    sets = np.array([[[0, 4, 8, 12]], [[4, 8, 16, S]], [[2, 4, 12, 16]]], dtype=np.int32)   # n_e = 3, one unit, kb = 4
+    assert _valid(oracle.vote(sets, 1, 0)[0]) == [0, 2, 4, 8, 12, 16]          # union
+    assert oracle.vote(sets, 1, 0).shape == (1, 12)
+    assert _valid(oracle.vote(sets, 3, 0)[0]) == [4]                           # intersection
+    assert _valid(oracle.vote(sets, 2, 0)[0]) == [4, 8, 12, 16]
+    # truncation to kb = 4 by votes: 4 has three votes, 8, 12 and 16 two, 0 and 2 one
+    assert list(oracle.vote(sets, 1, 1)[0]) == [4, 8, 12, 16]
+    # equal votes: the lower positions stay (kb = 2: 4, then 8 rather than 12 or 16)
+    pairs = np.array([[[4, 8]], [[4, 12]], [[8, 12]], [[16, 4]]], dtype=np.int32)
+    assert list(oracle.vote(pairs, 1, 1)[0]) == [4, 8]
+    assert list(oracle.vote(pairs, 4, 1)[0]) == [S, S]                         # nothing has four votes but 4 (three) -> none
+    # random sets against a Counter
+    rng = np.random.default_rng(3)
+    for n_e, kb, span in ((2, 3, 8), (4, 8, 20), (5, 16, 40), (8, 4, 6)):
+        units = 7
+        samples = np.full((n_e, units, kb), S, dtype=np.int32)
+        for e in range(n_e):
+            for u in range(units):
+                n = int(rng.integers(0, min(kb, span) + 1))
+                samples[e, u, :n] = np.sort(rng.choice(span, size=n, replace=False)) * 2
+        for theta in range(1, n_e + 1):
+            for tau in (0, 1):
+                out = oracle.vote(samples, theta, tau)
+                for u in range(units):
+                    want = _vote_by_counter(samples[:, u], theta, tau, kb)
+                    assert _valid(out[u]) == want and (out[u, len(want):] == S).all(), (n_e, kb, theta, tau, u)
+
+
 def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     """The oracle built with -fsanitize=address,undefined runs a set of problems that walks every code path (prefill and
     decode, ragged, paged with a token bank and the map of pages read, every scoring option, sink and window) without
@@ -609,7 +736,7 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
             for (T, q_len, bq, bk, kb, page, opts) in [
                     (97, 97, 4, 2, 8, 0, {{}}), (64, 64, 16, 1, 3, 0, dict(b_sq=2, rep_pos=1)),
                     (130, 1, 1, 2, 16, 4, dict(rep_pos=2, b_sk=2, n_sink=3, n_window=5)),
-                    (75, 20, 8, 4, 4, 8, dict(top_r=3, n_window=7)), (33, 33, 32, 2, 64, 0, {{}})]:
+                    (75, 20, 8, 4, 4, 8, dict(top_r=3, n_window=7, ens_sample=2, ens_seed=5, ens_r=3.0)), (33, 33, 32, 2, 64, 0, {{}})]:
                 B, Hq, Hkv, d = 2, 4, 2, 8
                 lens = rng.integers(max(q_len, T // 2), T + 1, size=B).astype(np.int32)
                 Q = rng.integers(-4, 5, size=(B, Hq, q_len, d)).astype(np.float32) / 8
@@ -631,6 +758,8 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
                 idx = oracle.mask_estimate(p, Q, K)
                 out = oracle.sparse_attn(p, Q, K, V, idx, 0.3)
                 res.append((idx.copy(), out.copy()))
+                votes = oracle.vote(np.stack([idx, idx[::-1].copy(), idx]), 2, 1)
+                res.append((votes, oracle.vote(np.stack([idx, idx[::-1].copy()]), 1, 0)))
             return res
         plain = run()
         oracle._lib = None
@@ -646,4 +775,4 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     env = dict(os.environ, LD_PRELOAD=preload, ASAN_OPTIONS="detect_leaks=0:abort_on_error=1", UBSAN_OPTIONS="halt_on_error=1")
     r = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-4000:]
-    assert "sanitized oracle agrees on 5 problems" in r.stdout
+    assert "sanitized oracle agrees on 10 problems" in r.stdout
