@@ -295,14 +295,27 @@ def measure(args, w, tag, steps, warmup, with_cpu):
     # scratch of the top-r pre-pass (a copy of Q), allocated once outside the timed region
     ws = torch.empty(x["Q"].numel() * x["Q"].element_size(), dtype=torch.uint8, device="cuda") if args.top_r else None
     refresh = max(1, args.refresh_period) if w.q_len < w.kv_len else 1
+    n_e = max(1, args.n_e)
+    k_attn = w.k
+    if n_e > 1:
+        # ensemble of masks: n_e samples and a vote per step; the attention then runs over the merged list
+        width = w.kb if args.tau else n_e * w.kb
+        k_attn = width * w.bk
+        idx = torch.empty((w.batch, w.n_q_heads, w.n_query_blocks, width), dtype=torch.int32, device="cuda")
+        ws_e = torch.empty(n_e * w.batch * w.n_q_heads * w.n_query_blocks * w.kb * 4 + 256, dtype=torch.uint8, device="cuda")
 
     def run_mask():
+        if n_e > 1:
+            hipattn.hip_mask_ensemble(x["Q"], x["K"], w.k, w.bq, w.bk, n_e, args.theta_vote, args.tau, 1234, args.r_e,
+                                      kv_lens=x["kv_lens"], page_table=x["page_table"], max_kv_len=max_len, flags=flags,
+                                      b_sq=args.b_sq, b_sk=args.b_sk, rep_pos=args.rep_pos, workspace=ws_e, indices=idx)
+            return
         hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, kv_lens=x["kv_lens"], page_table=x["page_table"],
                                   max_kv_len=max_len, flags=flags, indices=idx, b_sq=args.b_sq, b_sk=args.b_sk,
                                   rep_pos=args.rep_pos, top_r=args.top_r, workspace=ws, **bank)
 
     def run_attn():
-        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, w.k, w.bq, w.bk, kv_lens=x["kv_lens"],
+        hipattn.hip_sparse_attn(x["Q"], x["K"], x["V"], idx, k_attn, w.bq, w.bk, kv_lens=x["kv_lens"],
                                 page_table=x["page_table"], max_kv_len=max_len, flags=flags, out=out,
                                 n_sink=args.n_sink, n_window=args.n_window, **(bank_attn if bank else {}))
 
@@ -330,9 +343,11 @@ def measure(args, w, tag, steps, warmup, with_cpu):
     ms_mask, ms_attn = sum(t_mask) / len(t_mask), sum(t_attn) / len(t_attn)
 
     size = 2 if w.dtype == "bf16" else 4
-    mask_bytes = mask_algorithmic_bytes(w, kv_lens, args.rep_pos)
-    mask_flops = mask_score_flops(w, kv_lens, args.rep_pos, max(args.b_sq, 1), max(args.b_sk, 1))
-    attn_flops, attn_bytes = attn_algorithmic(w, kv_lens)
+    mask_bytes = n_e * mask_algorithmic_bytes(w, kv_lens, args.rep_pos)
+    mask_flops = n_e * mask_score_flops(w, kv_lens, args.rep_pos, max(args.b_sq, 1), max(args.b_sk, 1))
+    # (ensemble: the merged list is at most k_attn keys long; its real length depends on the data, so the
+    # attention's algorithmic figures are upper bounds there)
+    attn_flops, attn_bytes = attn_algorithmic(synth.scaled(w, k=k_attn), kv_lens)
     mask_gbs = mask_bytes / (ms_mask * 1e-3) / 1e9
     mask_tflops = mask_flops / (ms_mask * 1e-3) / 1e12
     attn_tflops = attn_flops / (ms_attn * 1e-3) / 1e12
@@ -406,7 +421,8 @@ def measure(args, w, tag, steps, warmup, with_cpu):
         "config": {"workload": w.name, "batch": w.batch, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "q_len": w.q_len, "kv_len": w.kv_len, "k": w.k, "bq": w.bq, "bk": w.bk,
                    "kernels": "generic" if args.generic else "tuned", "b_sq": args.b_sq, "b_sk": args.b_sk, "rep_pos": args.rep_pos, "top_r": args.top_r,
-                   "n_sink": args.n_sink, "n_window": args.n_window, "refresh_period": refresh},
+                   "n_sink": args.n_sink, "n_window": args.n_window, "refresh_period": refresh,
+                   "ensemble": {"n_e": n_e, "theta_vote": args.theta_vote, "tau": args.tau, "r_e": args.r_e} if n_e > 1 else None},
         "kernel_ms": {"mask_estimate": ms_mask, "sparse_attn": ms_attn},
         "kernel_ms_median": {"mask_estimate": t_mask[len(t_mask) // 2], "sparse_attn": t_attn[len(t_attn) // 2]},
         "kernel_ms_min": {"mask_estimate": t_mask[0], "sparse_attn": t_attn[0]},
@@ -474,6 +490,11 @@ def main():
     ap.add_argument("--dense-yardstick", action="store_true",
                     help="also time torch's dense causal attention on the same tensors (prefill workloads up to "
                          "128k tokens; external yardstick, not part of the path)")
+    ap.add_argument("--n-e", type=int, default=1,
+                    help="ensemble of masks: samples per step (default 1: the plain mask); the vote is part of the mask time")
+    ap.add_argument("--theta-vote", type=int, default=1, help="ensemble: votes a key block needs (1 = union)")
+    ap.add_argument("--tau", type=int, default=0, choices=[0, 1], help="ensemble: 1 truncates the merged list to k by votes")
+    ap.add_argument("--r-e", type=float, default=5.0, help="ensemble: size of the score perturbation")
     ap.add_argument("--no-gather-probe", dest="gather_probe", action="store_false",
                     help="skip the gather probe (the measured ceiling quoted next to the published ones)")
     ap.add_argument("--target-points", type=int, default=-1, choices=[-1, 0, 1],
@@ -490,7 +511,8 @@ def main():
     torch.cuda.set_device(0)
     plain = (args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 and args.page_size < 0
              and args.resident_frac < 0 and not args.generic and args.b_sq <= 1 and args.b_sk <= 1 and args.rep_pos == 0
-             and args.top_r == 0 and args.n_sink == 0 and args.n_window == 0 and args.refresh_period <= 1)
+             and args.top_r == 0 and args.n_sink == 0 and args.n_window == 0 and args.refresh_period <= 1
+             and args.n_e <= 1)
 
     def tag_of(workload, seq_len):
         # counter summaries under profiles/ exist for the named workloads as they stand and for C2's shape at 128k

@@ -57,6 +57,7 @@ enum {
     HIP_ATTN_EPAGE = -8,       /* page table given with page_size <= 0 or page_size % bk != 0; a backing   */
                                /* pool or a touched map without a page table                   */
     HIP_ATTN_EWORKSPACE = -9,  /* workspace_bytes below hip_workspace_bytes()                 */
+    HIP_ATTN_EENSEMBLE = -11,  /* n_e, theta_vote or n_e * k/bk out of range                              */
     HIP_ATTN_ESCRATCH = -10,   /* hip_mask_estimate_noalloc: hip_workspace_bytes() above the static scratch */
     HIP_ATTN_ELAUNCH = -1000   /* launch failure: code is HIP_ATTN_ELAUNCH - hipError_t       */
 };
@@ -135,6 +136,18 @@ typedef struct hip_problem {
      * left as they are, so the caller zeroes the map and may let it accumulate over calls: it is what a
      * cache manager needs to count hits and misses (compare with the table) and to pick the pages to load. */
     uint8_t *touched;
+    /* hip_mask_estimate only: ensemble sample (paper appendix "Ensemble Hierarchical Top-k Approximation": several
+     * masks are drawn "by adding randomness r_e to the branch direction" of a middle iteration, then voted on).
+     * ens_sample = 0 (default) is the plain mask.  A sample e > 0 differs in one round of the search, round
+     * R / 2 of the R = ceil(log2(ceil(Tb / (k/bk)))) rounds of a query block with Tb visible key blocks (rounds
+     * counted from 0): there the top-k selection compares score + ens_r * u instead of the score, u a draw on
+     * [-1, 1) fixed by (ens_seed, e, sequence, head, query block, representative block): the 32-bit finalizer of
+     * MurmurHash3, x ^= x >> 16; x *= 0x85ebca6b; x ^= x >> 13; x *= 0xc2b2ae35; x ^= x >> 16, is applied to
+     * ens_seed ^ 0x9e3779b9 and then, five times, to (previous result ^ next number); with n the top 24 bits of
+     * the last result, u = (n - 2^23) / 2^23.  Product and sum are single precision, each rounded once. */
+    int32_t ens_sample;
+    uint32_t ens_seed;
+    float ens_r;
 } hip_problem;
 
 /*
@@ -182,6 +195,30 @@ size_t hip_workspace_bytes(const hip_problem *p);
 #define HIP_ATTN_STATIC_SCRATCH_BYTES (8u << 20)
 int hip_mask_estimate_noalloc(const hip_problem *p, const void *Q, const void *K, int32_t *indices,
                               void *stream);
+
+/*
+ * Vote over an ensemble of masks (paper appendix "Ensemble Hierarchical Top-k Approximation", second step).
+ *   samples  device int32 [n_e][batch, n_q_heads, ceil(q_len/bq), k/bk]: n_e index arrays as hip_mask_estimate
+ *            writes them (every row ascending, then HIP_ATTN_SENTINEL padding; entries < 0 count as padding)
+ *   indices  device int32 [batch, n_q_heads, ceil(q_len/bq), width], width = k/bk if tau else n_e * k/bk:
+ *            per query block the positions held by at least theta_vote of the n_e rows (1 = union, n_e =
+ *            intersection), ascending, HIP_ATTN_SENTINEL-padded.  tau = 1 keeps at most k/bk of them: those with
+ *            more votes first, the lower position among equal votes.
+ * Only batch, n_q_heads, q_len, bq, k, bk of `p` are used.  1 <= n_e <= 16, n_e * k/bk <= 4096, 1 <= theta_vote.
+ * hip_sparse_attn takes the result with k set to width * bk (so width must stay within HIP_ATTN_MAX_KB).
+ */
+int hip_mask_vote(const hip_problem *p, const int32_t *samples, int32_t n_e, int32_t theta_vote, int32_t tau,
+                  int32_t *indices, void *stream);
+
+/*
+ * Ensemble mask in one call: samples 0 .. n_e - 1 of hip_mask_estimate (p->ens_sample is ignored; p->ens_seed
+ * and p->ens_r apply; sample 0 is the plain mask) into p->workspace, then hip_mask_vote into `indices`.
+ * p->workspace must hold hip_ensemble_workspace_bytes(p, n_e) bytes, 256-byte aligned: the n_e index arrays,
+ * after the scratch of the top_r option when that is in use.
+ */
+int hip_mask_ensemble(const hip_problem *p, const void *Q, const void *K, int32_t n_e, int32_t theta_vote,
+                      int32_t tau, int32_t *indices, void *stream);
+size_t hip_ensemble_workspace_bytes(const hip_problem *p, int32_t n_e);
 
 /* Static, human-readable text for a return code. */
 const char *hip_strerror(int code);

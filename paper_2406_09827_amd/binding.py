@@ -18,7 +18,8 @@ SENTINEL = 2**31 - 1
 F32, BF16 = 0, 1
 FORCE_GENERIC = 1
 
-EXPORTS = ("hip_mask_estimate", "hip_mask_estimate_noalloc", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
+EXPORTS = ("hip_mask_estimate", "hip_mask_estimate_noalloc", "hip_mask_vote", "hip_mask_ensemble",
+           "hip_ensemble_workspace_bytes", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")
 
 
 class HipProblem(ctypes.Structure):
@@ -35,6 +36,7 @@ class HipProblem(ctypes.Structure):
         ("b_sq", ctypes.c_int32), ("b_sk", ctypes.c_int32), ("rep_pos", ctypes.c_int32), ("top_r", ctypes.c_int32),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
         ("k_backing", ctypes.c_void_p), ("v_backing", ctypes.c_void_p), ("touched", ctypes.c_void_p),
+        ("ens_sample", ctypes.c_int32), ("ens_seed", ctypes.c_uint32), ("ens_r", ctypes.c_float),
     ]
 
 
@@ -54,6 +56,14 @@ def load() -> ctypes.CDLL:
                                           ctypes.c_void_p, ctypes.c_void_p]
         lib.hip_mask_estimate_noalloc.restype = ctypes.c_int
         lib.hip_mask_estimate_noalloc.argtypes = lib.hip_mask_estimate.argtypes
+        lib.hip_mask_vote.restype = ctypes.c_int
+        lib.hip_mask_vote.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        lib.hip_mask_ensemble.restype = ctypes.c_int
+        lib.hip_mask_ensemble.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        lib.hip_ensemble_workspace_bytes.restype = ctypes.c_size_t
+        lib.hip_ensemble_workspace_bytes.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_int32]
         lib.hip_sparse_attn.restype = ctypes.c_int
         lib.hip_sparse_attn.argtypes = [ctypes.POINTER(HipProblem), ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -139,12 +149,14 @@ def _stream(t: torch.Tensor) -> int:
 def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=None, max_kv_len=None,
                       flags: int = 0, indices: Optional[torch.Tensor] = None, b_sq: int = 1, b_sk: int = 1,
                       rep_pos: int = 0, top_r: int = 0, workspace: Optional[torch.Tensor] = None,
-                      k_backing: Optional[torch.Tensor] = None, touched: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      k_backing: Optional[torch.Tensor] = None, touched: Optional[torch.Tensor] = None,
+                      ens_sample: int = 0, ens_seed: int = 0, ens_r: float = 0.0) -> torch.Tensor:
     """int32 indices [B, Hq, ceil(Tq/bq), k/bk] of the selected key blocks (see include/hipattn.h)."""
     _need_gpu(Q, K, kv_lens, page_table, indices)
     lib = load()
     p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
     p.b_sq, p.b_sk, p.rep_pos, p.top_r = b_sq, b_sk, rep_pos, top_r
+    p.ens_sample, p.ens_seed, p.ens_r = ens_sample, ens_seed & 0xffffffff, ens_r
     _token_bank(p, K, page_table, k_backing, None, touched)
     need = lib.hip_workspace_bytes(ctypes.byref(p))
     if need:
@@ -158,6 +170,52 @@ def hip_mask_estimate(Q, K, k: int, bq: int, bk: int, kv_lens=None, page_table=N
     assert indices.dtype == torch.int32 and indices.is_contiguous()
     assert indices.numel() == p.batch * p.n_q_heads * nqb * (k // bk)
     rc = lib.hip_mask_estimate(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), indices.data_ptr(), _stream(Q))
+    if rc != 0:
+        raise HipAttnError(rc)
+    return indices
+
+
+def hip_mask_vote(samples: torch.Tensor, theta_vote: int, tau: int, bq: int, bk: int, q_len: int,
+                  indices: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Vote over samples [n_e, B, Hq, ceil(q_len/bq), k/bk] -> int32 [B, Hq, nqb, k/bk if tau else n_e * k/bk]."""
+    _need_gpu(samples, indices)
+    assert samples.dtype == torch.int32 and samples.is_contiguous() and samples.dim() == 5
+    n_e, B, Hq, nqb, kb = samples.shape
+    p = HipProblem()
+    p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim = B, Hq, 1, 128
+    p.q_len, p.max_kv_len, p.k, p.bq, p.bk, p.dtype = q_len, q_len, kb * bk, bq, bk, BF16
+    assert (q_len + bq - 1) // bq == nqb
+    width = kb if tau else n_e * kb
+    if indices is None:
+        indices = torch.empty((B, Hq, nqb, width), dtype=torch.int32, device=samples.device)
+    assert indices.dtype == torch.int32 and indices.is_contiguous() and indices.numel() == B * Hq * nqb * width
+    rc = load().hip_mask_vote(ctypes.byref(p), samples.data_ptr(), n_e, theta_vote, tau, indices.data_ptr(), _stream(samples))
+    if rc != 0:
+        raise HipAttnError(rc)
+    return indices
+
+
+def hip_mask_ensemble(Q, K, k: int, bq: int, bk: int, n_e: int, theta_vote: int, tau: int, ens_seed: int, ens_r: float,
+                      kv_lens=None, page_table=None, max_kv_len=None, flags: int = 0, b_sq: int = 1, b_sk: int = 1,
+                      rep_pos: int = 0, top_r: int = 0, workspace: Optional[torch.Tensor] = None,
+                      indices: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Ensemble mask: n_e samples of hip_mask_estimate (sample 0 = the plain mask) and the vote over them."""
+    _need_gpu(Q, K, kv_lens, page_table, indices, workspace)
+    lib = load()
+    p = make_problem(Q, K, k, bq, bk, kv_lens, page_table, max_kv_len, flags=flags)
+    p.b_sq, p.b_sk, p.rep_pos, p.top_r = b_sq, b_sk, rep_pos, top_r
+    p.ens_seed, p.ens_r = ens_seed & 0xffffffff, ens_r
+    need = lib.hip_ensemble_workspace_bytes(ctypes.byref(p), n_e)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=Q.device)
+    assert workspace.is_contiguous() and workspace.numel() * workspace.element_size() >= need
+    p.workspace, p.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    nqb = (p.q_len + bq - 1) // bq
+    width = (k // bk) if tau else n_e * (k // bk)
+    if indices is None:
+        indices = torch.empty((p.batch, p.n_q_heads, nqb, width), dtype=torch.int32, device=Q.device)
+    assert indices.dtype == torch.int32 and indices.is_contiguous() and indices.numel() == p.batch * p.n_q_heads * nqb * width
+    rc = lib.hip_mask_ensemble(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), n_e, theta_vote, tau, indices.data_ptr(), _stream(Q))
     if rc != 0:
         raise HipAttnError(rc)
     return indices

@@ -71,6 +71,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
     kp.b_sq = (p.b_sq > 1 && p.q_len > 1) ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
     kp.top_r = p.top_r >= p.head_dim ? 0 : p.top_r;
+    kp.ens_sample = p.ens_sample > 0 ? p.ens_sample : 0; kp.ens_seed = p.ens_seed; kp.ens_r = p.ens_r;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)
         for (kp.page_shift = 0; (1 << kp.page_shift) < p.page_size;) ++kp.page_shift;
@@ -147,6 +148,54 @@ int hip_mask_estimate(const hip_problem *p, const void *Q, const void *K, int32_
     return mask_estimate_impl(p, Q, K, indices, stream, false);
 }
 
+int hip_mask_vote(const hip_problem *p, const int32_t *samples, int32_t n_e, int32_t theta_vote, int32_t tau,
+                  int32_t *indices, void *stream)
+{
+    KParams kp;
+    int rc = prepare(p, kp);
+    if (rc != HIP_ATTN_OK) return rc;
+    if (!vote_supported(n_e, kp.kb) || theta_vote < 1) return HIP_ATTN_EENSEMBLE;
+    if (kp.batch == 0 || kp.q_len == 0) return HIP_ATTN_OK;
+    if (!samples || !indices) return HIP_ATTN_ENULL;
+    const int64_t n_units = (int64_t)kp.batch * kp.hq * kp.nqb;
+    return launch_result(launch_vote(samples, indices, n_units, n_e, kp.kb, theta_vote, tau ? 1 : 0,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+size_t hip_ensemble_workspace_bytes(const hip_problem *p, int32_t n_e)
+{
+    if (!p || n_e <= 0 || p->batch <= 0 || p->n_q_heads <= 0 || p->q_len <= 0 || p->bq <= 0 || p->bk <= 0 || p->k <= 0) return 0;
+    const size_t nqb = (size_t)((p->q_len + p->bq - 1) / p->bq);
+    const size_t one = (size_t)p->batch * (size_t)p->n_q_heads * nqb * (size_t)(p->k / p->bk) * sizeof(int32_t);
+    return align256(hip_workspace_bytes(p)) + (size_t)n_e * one;
+}
+
+int hip_mask_ensemble(const hip_problem *p, const void *Q, const void *K, int32_t n_e, int32_t theta_vote,
+                      int32_t tau, int32_t *indices, void *stream)
+{
+    KParams kp;
+    int rc = prepare(p, kp);
+    if (rc != HIP_ATTN_OK) return rc;
+    if (!vote_supported(n_e, kp.kb) || theta_vote < 1) return HIP_ATTN_EENSEMBLE;
+    if (kp.batch == 0 || kp.q_len == 0) return HIP_ATTN_OK;
+    if (!p->workspace || !indices) return HIP_ATTN_ENULL;
+    if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return HIP_ATTN_EALIGN;
+    if (p->workspace_bytes < hip_ensemble_workspace_bytes(p, n_e)) return HIP_ATTN_EWORKSPACE;
+    const size_t front = align256(hip_workspace_bytes(p));
+    const size_t one = (hip_ensemble_workspace_bytes(p, n_e) - front) / (size_t)n_e;
+    int32_t *samples = reinterpret_cast<int32_t *>(static_cast<char *>(p->workspace) + front);
+    hip_problem q = *p;
+    q.workspace_bytes = front;   // what is left to the top_r option
+    for (int e = 0; e < n_e; ++e) {
+        q.ens_sample = e;
+        rc = mask_estimate_impl(&q, Q, K, samples + (size_t)e * (one / sizeof(int32_t)), stream, false);
+        if (rc != HIP_ATTN_OK) return rc;
+    }
+    return hip_mask_vote(p, samples, n_e, theta_vote, tau, indices, stream);
+}
+
 int hip_mask_estimate_noalloc(const hip_problem *p, const void *Q, const void *K, int32_t *indices, void *stream)
 {
     return mask_estimate_impl(p, Q, K, indices, stream, true);
@@ -198,11 +247,12 @@ const char *hip_strerror(int code)
         case HIP_ATTN_EALIGN: return "pointer or stride not 16-byte aligned";
         case HIP_ATTN_EPAGE: return "invalid page table description (or a backing pool / touched map without a page table)";
         case HIP_ATTN_EWORKSPACE: return "workspace smaller than hip_workspace_bytes()";
+        case HIP_ATTN_EENSEMBLE: return "ensemble: n_e outside 1..16, theta_vote < 1, or n_e * k/bk above 4096";
         case HIP_ATTN_ESCRATCH: return "the problem needs more scratch than the library's static HIP_ATTN_STATIC_SCRATCH_BYTES";
         default: return code <= HIP_ATTN_ELAUNCH ? "kernel launch failed" : "unknown error";
     }
 }
 
-int hip_attn_version(void) { return 105; }
+int hip_attn_version(void) { return 106; }
 
 }  // extern "C"

@@ -27,6 +27,9 @@ struct KParams {
     int32_t b_sq, b_sk;        // mask estimation: row / key sampling strides of the block score (>= 1)
     int32_t rep_pos;           // mask estimation: representative block of a branch: 0 centre, 1 first, 2 last
     int32_t top_r;             // mask estimation: channels kept per query row, 0 = all
+    int32_t ens_sample;        // mask estimation: ensemble sample number, 0 = the plain mask
+    uint32_t ens_seed;         // mask estimation: seed of the ensemble samples' draws
+    float ens_r;               // mask estimation: size of the score perturbation of a sample > 0
     float sm_scale;
 };
 
@@ -123,6 +126,45 @@ __device__ __forceinline__ int lane_prefix_count(uint64_t mask)
 __device__ __forceinline__ int rep_block(int bs, int be, int rep_pos)
 {
     return rep_pos == 1 ? bs : rep_pos == 2 ? be - 1 : bs + ((be - bs) >> 1);
+}
+
+// ---- ensemble samples (paper appendix "Ensemble Hierarchical Top-k Approximation") ------------------
+// A sample e > 0 differs from the plain mask in ONE round of the search, the middle one (round R / 2 of the
+// R rounds the query block runs, counted from 0): there the top-kb selection compares score + r_e * u, u a
+// draw on [-1, 1) that depends only on (seed, sample, sequence, head, query block, representative block of
+// the branch): MurmurHash3's 32-bit finalizer absorbs these numbers one after the other and the top 24 bits
+// of the result, as an integer n, give u = (n - 2^23) / 2^23.  Product and sum are each rounded once to fp32.
+__device__ __forceinline__ uint32_t fmix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    return x;
+}
+// everything but the representative block absorbed
+__device__ __forceinline__ uint32_t ens_unit_hash(uint32_t seed, int sample, int b, int h, int qb)
+{
+    uint32_t x = fmix32(seed ^ 0x9e3779b9u);
+    x = fmix32(x ^ (uint32_t)sample);
+    x = fmix32(x ^ (uint32_t)b);
+    x = fmix32(x ^ (uint32_t)h);
+    return fmix32(x ^ (uint32_t)qb);
+}
+// The round of the search an ensemble sample perturbs, or -1 (plain mask): maxlen = longest initial node.
+__device__ __forceinline__ int ens_round_of(int sample, int maxlen)
+{
+    if (sample <= 0) return -1;
+    int rounds = 0;
+    for (; maxlen > 1; maxlen = (maxlen + 1) >> 1) ++rounds;
+    return rounds >> 1;
+}
+// The key the selection of the perturbed round compares, from the key of the branch's score (0 = empty slot).
+__device__ __forceinline__ uint32_t ens_key(uint32_t key, uint32_t unit_hash, int rep_blk, float r_e)
+{
+    if (key == 0u) return 0u;
+    const uint32_t bits = (key & 0x80000000u) ? (key ^ 0x80000000u) : ~key;  // inverse of score_key
+    const uint32_t x = fmix32(unit_hash ^ (uint32_t)rep_blk);
+    const float u = (float)((int)(x >> 8) - (1 << 23)) * (1.0f / 8388608.0f);   // exact
+    const float moved = __fadd_rn(__uint_as_float(bits), __fmul_rn(r_e, u));    // no fused multiply-add
+    return score_key(moved);
 }
 
 constexpr uint32_t kKeyNegInf = 0x007fffffu;  // score_key(-inf): a real branch without admissible pair

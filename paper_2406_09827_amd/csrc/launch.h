@@ -16,5 +16,7 @@ hipError_t launch_attn_decode(const KParams &p, hipStream_t st);
 hipError_t launch_attn_generic(const KParams &p, bool bf16, hipStream_t st);
 hipError_t launch_topr_mask(const KParams &p, bool bf16, void *dst, hipStream_t st);
 hipError_t launch_touch_attn(const KParams &p, hipStream_t st);
+bool vote_supported(int n_e, int kb);
+hipError_t launch_vote(const int32_t *samples, int32_t *out, int64_t n_units, int n_e, int kb, int theta, int tau, hipStream_t st);
 
 }  // namespace hipattn

@@ -102,7 +102,11 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     // one-block node is its own representative and the right half of a two-block node is the node's representative,
     // so the left children alone are scored)
     const int side = p.rep_pos == 1 ? 1 : 0;
-    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
+    // ensemble sample: the round whose selection compares perturbed scores (-1: none)
+    const int ens_round = ens_round_of(p.ens_sample, (Tb + kb - 1) / kb);
+    const uint32_t ens_hash = ens_round >= 0 ? ens_unit_hash(p.ens_seed, p.ens_sample, b, h, 0) : 0u;
+    int round = 0;
+    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1, ++round) {
         const int *ns = nds[own][cur], *ne = nde[own][cur];
         const uint32_t *nkey = nkey_s[own][cur];
         // work items of the scoring loop: every branch slot, or in a carry round one per node
@@ -201,7 +205,23 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         int dest[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
-        select_topk_ordered<E>(key, kb, keep, dest);
+        if (round == ens_round) {
+            // the selection sees the perturbed scores; key[] keeps the true ones (they are what a later round carries)
+            uint32_t ksel[E];
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+                ksel[i] = 0u;
+                if (key[i] != 0u) {
+                    const int slot = i * 64 + lane, node = slot >> 1;
+                    const int s = ns[node], e = ne[node];
+                    const int mid = s + ((e - s) >> 1);
+                    ksel[i] = ens_key(key[i], ens_hash, rep_block((slot & 1) ? mid : s, (slot & 1) ? e : mid, p.rep_pos), p.ens_r);
+                }
+            }
+            select_topk_ordered<E>(ksel, kb, keep, dest);
+        } else {
+            select_topk_ordered<E>(key, kb, keep, dest);
+        }
         int *ns2 = nds[own][cur ^ 1], *ne2 = nde[own][cur ^ 1];
         uint32_t *nkey2 = nkey_s[own][cur ^ 1];
 #pragma unroll

@@ -56,8 +56,12 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
     const T *Kbase = (const T *)p.K, *Kback = (const T *)p.Kback;
     const int grp = tid >> 4, l16 = tid & 15;
 
+    // ensemble sample: the round whose selection compares perturbed scores (-1: none)
+    const int ens_round = ens_round_of(p.ens_sample, a + (r ? 1 : 0));
+    const uint32_t ens_hash = ens_round >= 0 ? ens_unit_hash(p.ens_seed, p.ens_sample, b, h, qb) : 0u;
+    int round = 0;
     // maxlen bounds the longest node; one more round than strictly needed is a no-op
-    for (int maxlen = a + (r ? 1 : 0); maxlen > 1; maxlen = (maxlen + 1) >> 1) {
+    for (int maxlen = a + (r ? 1 : 0); maxlen > 1; maxlen = (maxlen + 1) >> 1, ++round) {
         // split every node into its left and right branch (slot 2j, 2j+1); left may be empty
         for (int j = tid; j < NB / 2; j += kThreads) {
             int s = 0, mid = 0, e = 0;
@@ -108,7 +112,11 @@ __global__ __launch_bounds__(kThreads) void mask_generic_kernel(KParams p)
         bool keep[E];
         int dest[E];
 #pragma unroll
-        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
+        for (int i = 0; i < E; ++i) {
+            key[i] = keys[i * 64 + lane];
+            if (round == ens_round && key[i] != 0u)
+                key[i] = ens_key(key[i], ens_hash, rep_block(br_s[i * 64 + lane], br_e[i * 64 + lane], p.rep_pos), p.ens_r);
+        }
         select_topk_ordered<E>(key, kb, keep, dest);
 #pragma unroll
         for (int i = 0; i < E; ++i) {

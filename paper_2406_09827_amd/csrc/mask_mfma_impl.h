@@ -390,7 +390,11 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) asm volatile("" :: "v"(qf[0][kk]));
     }
-    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1) {
+    // ensemble sample: the round whose selection compares perturbed scores (-1: none)
+    const int ens_round = ens_round_of(p.ens_sample, (Tb + kb - 1) / kb);
+    const uint32_t ens_hash = ens_round >= 0 ? ens_unit_hash(p.ens_seed, p.ens_sample, b, h, qb) : 0u;
+    int round = 0;
+    for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1, ++round) {
         // Pipeline: branch-table reads run three to four tiles ahead of the multiply, row loads two.
         // The loop body is straight-line code: tile numbers past the end are clamped to the last tile
         // (it is then loaded and scored again, which rewrites the same keys), because a load that is
@@ -536,7 +540,23 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
         int dest[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
-        select_topk_ordered<E>(key, kb, keep, dest);
+        if (round == ens_round) {
+            // the selection sees the perturbed scores; key[] keeps the true ones (they are what a later round carries)
+            uint32_t ksel[E];
+#pragma unroll
+            for (int i = 0; i < E; ++i) {
+                ksel[i] = 0u;
+                if (key[i] != 0u) {
+                    const int slot = i * 64 + lane, node = slot >> 1;
+                    const int s = ns[node], e = ne[node];
+                    const int mid = s + ((e - s) >> 1);
+                    ksel[i] = ens_key(key[i], ens_hash, rep_block((slot & 1) ? mid : s, (slot & 1) ? e : mid, p.rep_pos), p.ens_r);
+                }
+            }
+            select_topk_ordered<E>(ksel, kb, keep, dest);
+        } else {
+            select_topk_ordered<E>(key, kb, keep, dest);
+        }
         int cs[E], ce[E];
 #pragma unroll
         for (int i = 0; i < E; ++i) {
