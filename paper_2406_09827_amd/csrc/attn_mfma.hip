@@ -61,14 +61,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
     const int lg = lane / CPR, lc = lane % CPR;  // loading role: rows lg*NLD .. +NLD-1, chunk lc
 
     // ---- which (sequence, head, query block, query tile) this wave owns
-    const int64_t groups = (int64_t)p.batch * p.hkv;
-    const int64_t per_group = (int64_t)p.g * p.nqb * mtn;
-    int64_t group, o;
+    const uint32_t groups = (uint32_t)p.batch * (uint32_t)p.hkv;
+    const uint32_t per_group = (uint32_t)p.g * (uint32_t)p.nqb * (uint32_t)mtn;
+    uint32_t group, o;
     if (!place_item(xcd_map, blockIdx.x, SPLIT ? 1 : 4, SPLIT ? 0 : wave, per_group, groups, group, o)) return;
-    const int qb = p.nqb - 1 - (int)(o / (p.g * mtn));
-    const int rem = (int)(o % (p.g * mtn));
-    const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
-    const int h = hk * p.g + rem / mtn, mt = rem % mtn;
+    const uint32_t gm = (uint32_t)(p.g * mtn), oq = o / gm, rem = o - oq * gm;
+    const int qb = p.nqb - 1 - (int)oq;
+    const int b = (int)(group / (uint32_t)p.hkv), hk = (int)(group - (uint32_t)b * (uint32_t)p.hkv);
+    const int h = hk * p.g + (mtn == 2 ? (int)(rem >> 1) : (int)rem), mt = mtn == 2 ? (int)(rem & 1) : 0;
 
     const int kv_len = p.kv_lens ? p.kv_lens[b] : p.max_kv_len;
     const int row0 = qb * p.bq + mt * 32;
@@ -233,15 +233,23 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
         wave_lds_sync();
 
         if (flags & 1) {
-            // ---- S^T = K Q^T: A = key rows from the LDS tile (lane: key row col), B = queries
+            // ---- S^T = K Q^T: A = key rows from the LDS tile (lane: key row col), B = queries.  All operand reads
+            // are issued before the first multiply (one LDS latency per tile, not one per k-step); the wave
+            // raises its priority while it feeds the matrix pipe, so that of two waves on a SIMD one multiplies
+            // while the other runs its softmax arithmetic instead of both queueing on the same unit.
             f32x16 sacc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+            uint4 kv[KS];
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const uint4 kv = *(const uint4 *)(kt + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv), qf[kk], sacc, 0, 0, 0);
-            }
+            for (int kk = 0; kk < KS; ++kk)
+                kv[kk] = *(const uint4 *)(kt + col * ROWB + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4));
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kv[kk]), qf[kk], sacc, 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
 
             // ---- online softmax for query `col` (both half-waves hold the same query)
             float s[16], mx = -INFINITY;
@@ -280,11 +288,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
             const float m_new = mx > m_run + kSlack ? mx : m_run;
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-            float lsum = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, -m_safe));
-                lsum += s[r];
+            for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, -m_safe));
+            // P^T as B operand of the two 16-key steps (registers 8*st .. 8*st+7), rounded to bf16.  The row sum l
+            // is taken over the ROUNDED probabilities (v_dot2_f32_bf16 against ones, fp32 accumulation), so that
+            // numerator and denominator of the output carry the same weights: the rounding of P then perturbs the
+            // weights of a weighted mean by 2^-9 relative instead of adding an error of that size to the output.
+            bf16x8 pb[2];
+            float lsum = 0.f;
+            {
+                const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    uint32_t hi[4];
+#pragma unroll
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        hi[e2] = pack_bf16(s[8 * st + 2 * e2], s[8 * st + 2 * e2 + 1]);
+                        lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, hi[e2]), ones, lsum, false);
+                    }
+                    pb[st] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+                }
             }
             l_run = l_run * alpha + lsum;
             m_run = m_new;
@@ -293,21 +316,6 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                 for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[ct][r] *= alpha;
-            }
-            // P^T as B operand of the two 16-key steps (registers 8*st .. 8*st+7), carried as a
-            // two-term bf16 expansion p = hi + lo so that rounding P does not limit the output
-            bf16x8 pb[2], pl[2];
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                uint32_t hi[4], lo[4];
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    const float a0 = s[8 * st + 2 * e2], a1 = s[8 * st + 2 * e2 + 1];
-                    hi[e2] = pack_bf16(a0, a1);
-                    lo[e2] = pack_bf16(a0 - __uint_as_float(hi[e2] << 16), a1 - __uint_as_float(hi[e2] & 0xffff0000u));
-                }
-                pb[st] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-                pl[st] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
             }
 
             // ---- O^T += V^T P^T: value tile read back channel-major with the LDS transpose read.
@@ -331,10 +339,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) v
                     }
                     // the CT accumulators are independent: interleave them so that no multiply waits
                     // for the one before it
+                    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
                     for (int ct = 0; ct < CT; ++ct) oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ct], pb[st], oacc[ct], 0, 0, 0);
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ct], pl[st], oacc[ct], 0, 0, 0);
+                    __builtin_amdgcn_s_setprio(0);
                 }
             }
         }
@@ -428,6 +436,10 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
         else if (mode == 0) hipLaunchKernelGGL((attn_mfma_kernel<DV, 0, SP>), grid, block, 0, st, p, log_bk, mtn, xcd_map); \
         else hipLaunchKernelGGL((attn_mfma_kernel<DV, 2, SP>), grid, block, 0, st, p, log_bk, mtn, xcd_map);                \
     } while (0)
+    if (p.d == 128 && p.kb <= 1024) {
+        // head dim 128: the variant that loads the gathered rows straight into LDS (attn_mfma_direct.hip)
+        return launch_attn_mfma_direct(p, grid, log_bk, mtn, xcd_map, mode, split, st);
+    }
     if (p.d == 64) {
         if (split) HIPATTN_LAUNCH(64, true); else HIPATTN_LAUNCH(64, false);
     } else {

@@ -240,22 +240,25 @@ __device__ __forceinline__ void wave_lds_sync()
 // x % gc share a group (8 / gc of them, each taking every (8/gc)-th workgroup of it) and the groups are
 // gone through gc at a time - few enough that the rows being read fit the memory-side cache.
 // upw = work items per workgroup, unit = this wave's item inside the workgroup.  False: nothing to do.
-__device__ __forceinline__ bool place_item(int xcd_map, int64_t bid, int upw, int unit, int64_t per_group, int64_t groups,
-                                           int64_t &group, int64_t &o)
+// (32-bit arithmetic: a launch covers fewer than 2^32 work items, the launchers check; 64-bit divisions here cost
+// every wave several hundred scalar instructions before it starts.)
+__device__ __forceinline__ bool place_item(int xcd_map, uint32_t bid, int upw, int unit, uint32_t per_group, uint32_t groups,
+                                           uint32_t &group, uint32_t &o)
 {
     if (!xcd_map) {
-        const int64_t lin = bid * upw + unit;
+        const uint32_t lin = bid * (uint32_t)upw + (uint32_t)unit;
         group = lin / per_group;
-        o = lin % per_group;
+        o = lin - group * per_group;
         return group < groups;
     }
-    const int gc = xcd_map, s = 8 / gc, x = (int)(bid & 7);
-    const int64_t q = bid >> 3;
-    const int64_t wpg = per_group / upw;       // workgroups per group
-    const int64_t wpp = (wpg + s - 1) / s;     // per XCD and group
-    const int64_t w_g = (q % wpp) * s + x / gc;
-    group = (q / wpp) * gc + x % gc;
-    o = w_g * upw + unit;
+    // gc = xcd_map is 1, 2, 4 or 8; upw is 1 or 4
+    const uint32_t lgc = (uint32_t)__builtin_ctz((uint32_t)xcd_map), ls = 3u - lgc, x = bid & 7u, q = bid >> 3;
+    const uint32_t wpg = upw == 4 ? per_group >> 2 : per_group;   // workgroups per group
+    const uint32_t wpp = (wpg + (1u << ls) - 1u) >> ls;            // per XCD and group
+    const uint32_t qd = q / wpp, qm = q - qd * wpp;
+    const uint32_t w_g = (qm << ls) + (x >> lgc);
+    group = (qd << lgc) + (x & ((1u << lgc) - 1u));
+    o = w_g * (uint32_t)upw + (uint32_t)unit;
     return group < groups && w_g < wpg;
 }
 

@@ -9,6 +9,7 @@ bool mask_mfma_supported(const KParams &p, bool bf16);
 hipError_t launch_mask_mfma(const KParams &p, hipStream_t st);
 bool attn_mfma_supported(const KParams &p, bool bf16);
 hipError_t launch_attn_mfma(const KParams &p, hipStream_t st);
+hipError_t launch_attn_mfma_direct(const KParams &p, dim3 grid, int log_bk, int mtn, int xcd_map, int mode, bool split, hipStream_t st);
 bool mask_decode_supported(const KParams &p, bool bf16);
 hipError_t launch_mask_decode(const KParams &p, hipStream_t st);
 bool attn_decode_supported(const KParams &p, bool bf16);

@@ -98,13 +98,14 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
     // ---- which (sequence, head, query block) this wave owns.  With `xcd_map` the workgroups an
     // XCD receives (blockIdx.x % 8) all read the same KV head; query blocks go from the longest
     // prefix down, the query heads of a KV group are adjacent.
-    const int64_t groups = (int64_t)p.batch * p.hkv;
-    const int64_t per_group = (int64_t)p.g * p.nqb;
-    int64_t group, o;
+    const uint32_t groups = (uint32_t)p.batch * (uint32_t)p.hkv;
+    const uint32_t per_group = (uint32_t)p.g * (uint32_t)p.nqb;
+    uint32_t group, o;
     if (!place_item(xcd_map, blockIdx.x, SPLIT ? 1 : 4, SPLIT ? 0 : wave, per_group, groups, group, o)) return;
-    const int qb = p.nqb - 1 - (int)(o / p.g);
-    const int hk = (int)(group % p.hkv), b = (int)(group / p.hkv);
-    const int h = hk * p.g + (int)(o % p.g);
+    const uint32_t oq = o / (uint32_t)p.g;
+    const int qb = p.nqb - 1 - (int)oq;
+    const int b = (int)(group / (uint32_t)p.hkv), hk = (int)(group - (uint32_t)b * (uint32_t)p.hkv);
+    const int h = hk * p.g + (int)(o - oq * (uint32_t)p.g);
     const int kb = p.kb;
     // sampling strides of the block score are powers of two here: key row n of a block is its key
     // n << ks (ks = log2 b_sk), query row i of the operand is row i << qs of the block (qs = log2 b_sq)
