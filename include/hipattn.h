@@ -22,7 +22,7 @@
  *   - Return value: HIP_ATTN_OK (0), a negative HIP_ATTN_E* argument error detected before
  *     any launch, or HIP_ATTN_ELAUNCH - (hipError_t) for a failed launch.  Nothing is
  *     printed; NaN/Inf inputs give unspecified indices.
- *   - Re-entrant; no mutable global state.
+ *   - Re-entrant; no mutable global state, except for hip_mask_estimate_noalloc (its static scratch, see there).
  *
  * Conventions (0-based):
  *   kb      = k / bk                       key blocks kept per query block
