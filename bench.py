@@ -272,7 +272,7 @@ def measure(args, w, tag, steps, warmup, with_cpu):
     import paper_2406_09827_amd as hipattn
     from paper_2406_09827_amd import synth
 
-    flags = hipattn.FORCE_GENERIC if args.generic else 0
+    flags = (hipattn.FORCE_GENERIC if args.generic else 0) | (hipattn.binding.NO_SHARED_ROUND if args.no_shared_round else 0)
     t0 = time.perf_counter()
     x = synth.make_inputs(w, device="cuda", threads=16)
     torch.cuda.synchronize()
@@ -458,6 +458,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "pd", "ps"])
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time; 0 disables")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
+    ap.add_argument("--no-shared-round", action="store_true",
+                    help="prefill mask estimation: every head gathers the first round's key tiles itself (A/B measurement)")
     ap.add_argument("--b-sq", type=int, default=1, help="query-row sampling stride of the block score (default: all rows)")
     ap.add_argument("--b-sk", type=int, default=1, help="key sampling stride of the block score (default: all keys)")
     ap.add_argument("--rep-pos", type=int, default=0, choices=[0, 1, 2],
@@ -512,7 +514,7 @@ def main():
     plain = (args.k == 0 and args.bk == 0 and args.bq == 0 and args.q_len == 0 and args.page_size < 0
              and args.resident_frac < 0 and not args.generic and args.b_sq <= 1 and args.b_sk <= 1 and args.rep_pos == 0
              and args.top_r == 0 and args.n_sink == 0 and args.n_window == 0 and args.refresh_period <= 1
-             and args.n_e <= 1)
+             and args.n_e <= 1 and not args.no_shared_round)
 
     def tag_of(workload, seq_len):
         # counter summaries under profiles/ exist for the named workloads as they stand and for C2's shape at 128k

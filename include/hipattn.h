@@ -67,7 +67,9 @@ enum { HIP_ATTN_REP_CENTER = 0, HIP_ATTN_REP_FIRST = 1, HIP_ATTN_REP_LAST = 2 };
 
 /* flags */
 enum {
-    HIP_ATTN_FORCE_GENERIC = 1 /* use the shape-generic kernels even where a tuned one exists */
+    HIP_ATTN_FORCE_GENERIC = 1, /* use the shape-generic kernels even where a tuned one exists */
+    HIP_ATTN_NO_SHARED_ROUND = 2 /* prefill mask estimation: every head gathers the first round's key tiles itself, */
+                                 /* even where the heads of a KV group could share them (A/B measurements)          */
 };
 
 #define HIP_ATTN_MAX_KB 1024   /* largest k/bk                                                */

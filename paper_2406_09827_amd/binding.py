@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libhipattn.so")
 SENTINEL = 2**31 - 1
 F32, BF16 = 0, 1
 FORCE_GENERIC = 1
+NO_SHARED_ROUND = 2
 
 EXPORTS = ("hip_mask_estimate", "hip_mask_estimate_noalloc", "hip_mask_vote", "hip_mask_ensemble",
            "hip_ensemble_workspace_bytes", "hip_sparse_attn", "hip_workspace_bytes", "hip_strerror", "hip_attn_version")

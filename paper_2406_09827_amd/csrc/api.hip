@@ -71,6 +71,7 @@ int prepare(const hip_problem *hp, KParams &kp)
     kp.n_sink = p.n_sink; kp.n_window = p.n_window;
     kp.b_sq = (p.b_sq > 1 && p.q_len > 1) ? p.b_sq : 1; kp.b_sk = p.b_sk > 1 ? p.b_sk : 1; kp.rep_pos = p.rep_pos;
     kp.top_r = p.top_r >= p.head_dim ? 0 : p.top_r;
+    kp.flags = p.flags;
     kp.ens_sample = p.ens_sample > 0 ? p.ens_sample : 0; kp.ens_seed = p.ens_seed; kp.ens_r = p.ens_r;
     kp.page_shift = -1;
     if (p.page_table && (p.page_size & (p.page_size - 1)) == 0)

@@ -31,6 +31,7 @@ struct KParams {
     uint32_t ens_seed;         // mask estimation: seed of the ensemble samples' draws
     float ens_r;               // mask estimation: size of the score perturbation of a sample > 0
     float sm_scale;
+    int32_t flags;             // HIP_ATTN_* flags of the call
 };
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits

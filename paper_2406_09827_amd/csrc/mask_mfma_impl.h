@@ -51,9 +51,13 @@ __device__ __forceinline__ float max_half_swap(float v)
 // each and run the selection redundantly (for launches with too few work items to fill the GPU wave by wave)
 // DIRECT: the key rows go from memory straight into LDS (global_load_lds_dwordx4) instead of through registers and
 // ds_write; see the tile loop.  One query tile, 512 branch slots, contiguous K only.
-template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false>
+// SHARE4 (with DIRECT): the four waves of a workgroup are four query heads of ONE (sequence, kv head, query block).  In
+// the first round they all score the same representative blocks (the initial nodes depend on the lengths only), so they
+// go through that round in step: each tile is loaded once, by one of the four waves, and read by all of them.
+template <int MT, int E, int D, bool PAGED, int LB, bool SPLIT = false, bool DIRECT = false, bool SHARE4 = false>
 __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
 {
+    static_assert(!SHARE4 || (DIRECT && !PAGED && !SPLIT), "shared first round: direct-to-LDS variant over contiguous keys");
     static_assert(!DIRECT || (MT == 1 && E <= 16 && !SPLIT && (!PAGED || E == 8)), "the direct-to-LDS variant: one query tile, up to 1024 slots (512 over a paged pool)");
     constexpr int NB = 64 * E;     // branch slots
     constexpr int KS = D / 16;     // MFMA k-steps per key row
@@ -472,6 +476,50 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     }
                     read_meta(next_meta_tile, mt_);
                 };
+                if (SHARE4 && round == 0) {
+                    // First round, shared: tile t is loaded by wave t % 4 into ITS buffer (three steps ahead) and read
+                    // by all four waves.  One barrier per step: it says that tile t has landed (its owner waited for
+                    // it) and that every wave has the operands of tile t-1 in registers, so that buffer may be refilled.
+                    const uint32_t ring0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)tile_buf[0];
+                    meta_t ml;
+                    if (wave < nt) {
+                        read_meta(wave, ml);
+#pragma unroll
+                        for (int j = 0; j < NLD; ++j) issue_row(ml, 0, j);
+                    }
+                    for (int t = 0; t < nt; ++t) {
+                        const int ow = t & 3;
+                        if (wave == ow) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                        __builtin_amdgcn_s_barrier();
+                        uint4 kv[KS];
+                        {
+                            const uint32_t base = ring0 + ow * TILEB + (RPI * (col % NLD) + col / NLD) * ROWB;
+#pragma unroll
+                            for (int kk = 0; kk < KS; ++kk)
+                                asm volatile("ds_read_b128 %0, %1" : "=v"(kv[kk]) : "v"(base + (((kk * 2 + hh) ^ (col & (CPR - 1))) << 4)) : "memory");
+                        }
+                        meta_t ms;
+                        int tcur, scur;
+                        read_meta(t, ms);
+                        row_info(ms, tcur, scur);
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (t >= 1 && wave == ((t - 1) & 3) && t + 3 < nt) {
+                            read_meta(t + 3, ml);
+#pragma unroll
+                            for (int j = 0; j < NLD; ++j) issue_row(ml, 0, j);
+                        }
+                        acc_t A;
+                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int kk = 0; kk < KS; ++kk)
+                            A.a[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[0][kk], __builtin_bit_cast(bf16x8, kv[kk]), kk == 0 ? zero : A.a[0], 0, 0, 0);
+                        score_finish(A, tcur, scur);
+                    }
+                    // the node ranges go back into the tile buffers next: not before every wave has read its last tiles
+                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                } else {
                 meta_t m0, m1;
                 int tc, sc, tn, sn;
                 read_meta(tile_of(0), m0);
@@ -491,6 +539,7 @@ __device__ __forceinline__ void mask_mfma_body(const KParams &p, int xcd_map)
                     score_finish(B, tn, sn);
                 }
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
             }
 #pragma unroll
             for (int i = 0; i < E / 2; ++i) { ns[i * 64 + lane] = sv[i]; ne[i * 64 + lane] = sv[E / 2 + i]; }
@@ -640,6 +689,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
     mask_mfma_body<1, 8, D, false, LB, false, true>(p, xcd_map);
 }
 template <int D, int LB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct_shared(KParams p, int xcd_map)
+{
+    mask_mfma_body<1, 8, D, false, LB, false, true, true>(p, xcd_map);
+}
+template <int D, int LB>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void mask_mfma_kernel_q32_direct_paged(KParams p, int xcd_map)
 {
     mask_mfma_body<1, 8, D, true, LB, false, true>(p, xcd_map);
@@ -699,6 +753,9 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
         const bool direct_paged = p.page_table && p.kb <= 256 && p.max_pages <= 1024 && one_sequence_per_workgroup &&
                                   (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
         if (direct_paged) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_paged<D, LB>), grid, block, 0, st, p, xcd_map);
+        // (the four work items of a workgroup are then four heads of one query block: they share the first round's tiles)
+        else if (direct && p.kb <= 256 && one_sequence_per_workgroup && p.g % 4 == 0 && !(p.flags & 2))
+            hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_shared<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (direct && p.kb <= 256) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (direct && p.kb <= 512) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_1k<D, LB>), grid, block, 0, st, p, xcd_map);
         else if (p.kb <= 256) HIPATTN_LAUNCH(mask_mfma_kernel_q32, 8);
