@@ -587,3 +587,27 @@ def test_blocks_of_8_and_16_keys(integer):
     U.run_case(wd, 0, n_sink=5, n_window=21)
     U.run_case(synth.scaled(wd, bk=16, k=4096, page_size=64, head_dim=64), 0, b_sk=2, rep_pos=1, n_window=50)
     U.run_case(synth.scaled(wd, batch=700, n_q_heads=2, n_kv_heads=1, kv_len=3000, ragged=(400, 3000), k=256), 0)   # wave-per-problem variants
+
+
+@pytest.mark.parametrize("bk,b_sk,g,rep_pos,b_sq", [(1, 1, 4, 0, 1), (2, 2, 4, 0, 1), (2, 1, 4, 2, 2), (4, 1, 8, 0, 1), (8, 1, 4, 1, 1),
+                                                    (2, 1, 8, 0, 1)])
+def test_first_round_shared_by_the_heads_of_a_kv_group(bk, b_sk, g, rep_pos, b_sq):
+    # more than 512 work items with g a multiple of 4: the four waves of a workgroup are four heads of one query block and
+    # go through the first round in step, each tile loaded once (1, 2, 4 and 8 scored rows per block; a ragged last query
+    # block; the ensemble's perturbed round, which is the first one for short prefixes).  Against the oracle, and bit for
+    # bit against the same call with every head gathering for itself.
+    import paper_2406_09827_amd as hipattn
+    T = 4500 + 13
+    for integer in (True, False):
+        w = synth.Workload("shared_round", 1, g, 1, 128, T, T, 96 * bk, 32, bk, "bf16", rho=0.95, spike_every=1024, integer=integer, seed=120 + bk)
+        nqb = w.n_query_blocks
+        assert g * nqb > 512
+        units = [(0, h, qb) for h in range(g) for qb in (3, 4, 7, 12, 40, nqb // 2, nqb - 2, nqb - 1)]
+        U.run_case(w, 0, units=units, rep_pos=rep_pos, b_sq=b_sq, b_sk=b_sk)
+        x = synth.make_inputs(w, device="cuda", threads=4)
+        for ens in (0, 2):
+            kw = dict(b_sq=b_sq, b_sk=b_sk, rep_pos=rep_pos, ens_sample=ens, ens_seed=5, ens_r=4.0)
+            a = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, **kw)
+            b = hipattn.hip_mask_estimate(x["Q"], x["K"], w.k, w.bq, w.bk, flags=hipattn.binding.NO_SHARED_ROUND, **kw)
+            torch.cuda.synchronize()
+            assert torch.equal(a, b)
