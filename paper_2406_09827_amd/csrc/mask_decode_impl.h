@@ -32,7 +32,7 @@ namespace hipattn {
 //                redundantly and write a quarter of the survivors each.  Used at small batch,
 //                where one wave per SIMD cannot keep enough loads in flight.
 template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xcd_map)
+__global__ __launch_bounds__(kThreads, (E == 16 && ROWS == 8 && !SPLIT) ? 3 : 1) void mask_decode_kernel(KParams p, int xcd_map)
 {
     constexpr int NB = 64 * E;
     constexpr int LPR = D / 8;        // lanes per key row
@@ -41,9 +41,10 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     typedef uint32_t stage_t __attribute__((ext_vector_type(4 * U * BK)));
     constexpr int NW = SPLIT ? 1 : 4;  // private copies of the per-problem LDS state
     constexpr int WS = SPLIT ? 4 : 1;  // waves sharing one problem
-    __shared__ uint32_t keys_s[NW][NB];
-    __shared__ int nds[NW][2][NB / 2], nde[NW][2][NB / 2];
-    __shared__ uint32_t nkey_s[NW][2][NB / 2];  // score key of the branch that became each node
+    // Two buffers of NB words swap roles every round: one holds the node list (NB/2 starts, then NB/2 ends), the other
+    // receives the round's score keys and, once the selection has them in registers, the next node list.
+    __shared__ uint32_t buf_s[NW][2][NB];
+    __shared__ uint32_t nkey_s[NW][NB / 2];  // score key of the branch that became each node
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // (uniform: what follows from it stays in scalar registers)
     const int grp = lane / LPR, lc = lane % LPR;
@@ -81,13 +82,12 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     const int tix = SPLIT ? (int)threadIdx.x : lane, tn = SPLIT ? kThreads : 64;
 
     const uint4 qv = *(const uint4 *)((const bf16_t *)p.Q + (int64_t)b * p.qs_b + (int64_t)h * p.qs_h + lc * 8);
-    uint32_t *keys = keys_s[own];
-    for (int i = tix; i < NB; i += tn) keys[i] = 0;
     {
+        int *ns0 = (int *)buf_s[own][0], *ne0 = ns0 + NB / 2;
         const int a = Tb / kb, r = Tb % kb;
         for (int j = tix; j < kb; j += tn) {
-            nds[own][0][j] = chunk_bound(j, a, r, kb);
-            nde[own][0][j] = chunk_bound(j + 1, a, r, kb);
+            ns0[j] = chunk_bound(j, a, r, kb);
+            ne0[j] = chunk_bound(j + 1, a, r, kb);
         }
     }
     sync_problem();
@@ -107,8 +107,9 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
     const uint32_t ens_hash = ens_round >= 0 ? ens_unit_hash(p.ens_seed, p.ens_sample, b, h, 0) : 0u;
     int round = 0;
     for (int maxlen = (Tb + kb - 1) / kb; maxlen > 1; maxlen = (maxlen + 1) >> 1, ++round) {
-        const int *ns = nds[own][cur], *ne = nde[own][cur];
-        const uint32_t *nkey = nkey_s[own][cur];
+        const int *ns = (const int *)buf_s[own][cur], *ne = ns + NB / 2;
+        uint32_t *keys = buf_s[own][cur ^ 1];  // every slot below 2 kb is written by the scoring loop
+        uint32_t *nkey = nkey_s[own];
         // work items of the scoring loop: every branch slot, or in a carry round one per node
         const int n_items = carry ? kb : 2 * kb;
 
@@ -188,6 +189,9 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         }
         sync_problem();
 
+        uint32_t key[E];
+#pragma unroll
+        for (int i = 0; i < E; ++i) key[i] = i * 64 + lane < 2 * kb ? keys[i * 64 + lane] : 0u;
         if (PAGED && p.touched) {
             // pages read this round: the representative block of every real branch (a branch whose score was
             // carried over had the same block read in an earlier round)
@@ -200,11 +204,10 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
                 }
             }
         }
-        uint32_t key[E];
+        // the survivors go where the keys were: every wave of the problem has to hold its copy of them first
+        if (SPLIT) __syncthreads();
         bool keep[E];
         int dest[E];
-#pragma unroll
-        for (int i = 0; i < E; ++i) key[i] = keys[i * 64 + lane];
         if (round == ens_round) {
             // the selection sees the perturbed scores; key[] keeps the true ones (they are what a later round carries)
             uint32_t ksel[E];
@@ -222,8 +225,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         } else {
             select_topk_ordered<E>(key, kb, keep, dest);
         }
-        int *ns2 = nds[own][cur ^ 1], *ne2 = nde[own][cur ^ 1];
-        uint32_t *nkey2 = nkey_s[own][cur ^ 1];
+        int *ns2 = (int *)keys, *ne2 = ns2 + NB / 2;
 #pragma unroll
         for (int i = 0; i < E; ++i) {
             if (keep[i] && (!SPLIT || (i & 3) == wave)) {
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
                 const int mid = s + ((e - s) >> 1);
                 ns2[dest[i]] = (slot & 1) ? mid : s;
                 ne2[dest[i]] = (slot & 1) ? e : mid;
-                nkey2[dest[i]] = key[i];
+                nkey[dest[i]] = key[i];
             }
         }
         cur ^= 1;
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void mask_decode_kernel(KParams p, int xc
         sync_problem();
     }
 
-    const int *ns = nds[own][cur];
+    const int *ns = (const int *)buf_s[own][cur];
     for (int j = tix; j < kb; j += tn) out[j] = ns[j] * bk;
 }
 
@@ -275,7 +277,9 @@ static hipError_t launch_e(const KParams &p, hipStream_t st)
         return launch_r<BK, D, 8, true>(p, dim3((unsigned)problems), xcd_map, st);
     }
     dim3 grid((unsigned)((problems + 3) / 4));
-    if (problems >= 4096) return launch_r<BK, D, 8, false>(p, grid, 0, st);
+    // Stages of 16 rows take about 240 registers: two waves per SIMD, two workgroups per compute unit.  With more than
+    // 512 workgroups, or with the selection state of kb > 256 on top, stages of 8 rows keep more waves resident.
+    if (grid.x > 512 || p.kb > 256) return launch_r<BK, D, 8, false>(p, grid, 0, st);
     return launch_r<BK, D, 16, false>(p, grid, 0, st);
 }
 
