@@ -426,8 +426,8 @@ hipError_t launch_attn_mfma(const KParams &p, hipStream_t st)
     if (waves == 0) return hipSuccess;
     // few work items (a quarter of the GPU's wave slots or less): a workgroup per work item, four waves share its key tiles
     const bool split = waves <= 512;
-    // groups worked on at a time: as many as keep their key and value rows inside the memory-side cache
-    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 4) : 0;
+    // groups worked on at a time (measured: all eight up to 128k tokens at head dim 128, four at 256k, one at a million)
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 4, 768LL << 20) : 0;
     dim3 grid((unsigned)placed_workgroups(xcd_map, split ? 1 : 4, per_group, groups)), block(kThreads);
     const int mode = p.page_table ? 1 : ((int64_t)p.max_kv_len * p.ks_r * 2 < (1LL << 32) ? 0 : 2);
 #define HIPATTN_LAUNCH(DV, SP)                                                                                  \

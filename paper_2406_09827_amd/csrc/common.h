@@ -263,8 +263,10 @@ __device__ __forceinline__ bool place_item(int xcd_map, uint32_t bid, int upw, i
     return group < groups && w_g < wpg;
 }
 
-// Host side: the launch size that goes with place_item, and how many groups to work on at a time so that
-// gc * bytes_per_group stays below what the 256 MB memory-side cache holds comfortably.
+// Host side: the launch size that goes with place_item, and how many groups to work on at a time: the largest
+// power of two up to 8 with gc * bytes_per_group <= budget.  Fewer groups at a time keep the rows being read inside
+// the 256 MB memory-side cache, more of them give every XCD's L2 a kv head of its own; where the balance lies was
+// measured per kernel (mask estimation: 160 MB; sparse attention, which reads every gathered row once: 768 MB).
 inline int64_t placed_workgroups(int xcd_map, int upw, int64_t per_group, int64_t groups)
 {
     if (!xcd_map) return (groups * per_group + upw - 1) / upw;
@@ -272,10 +274,10 @@ inline int64_t placed_workgroups(int xcd_map, int upw, int64_t per_group, int64_
     const int64_t wpg = per_group / upw, wpp = (wpg + s - 1) / s;
     return 8 * (groups / gc) * wpp;
 }
-inline int groups_at_a_time(int64_t bytes_per_group)
+inline int groups_at_a_time(int64_t bytes_per_group, int64_t budget_bytes)
 {
     int gc = 8;
-    while (gc > 1 && gc * bytes_per_group > (160LL << 20)) gc >>= 1;
+    while (gc > 1 && gc * bytes_per_group > budget_bytes) gc >>= 1;
     return gc;
 }
 

@@ -781,7 +781,7 @@ template <int LB> hipError_t launch_mask_mfma_lb(const KParams &p, hipStream_t s
     // waves sharing its tiles; measured faster up to 512 work items, level from there to 1024.
     const bool split = units <= 512 && p.kb <= 512;
     // groups worked on at a time: as many as keep the key rows in flight inside the memory-side cache
-    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 2) : 0;
+    const int xcd_map = (groups % 8 == 0 && (split || per_group % 4 == 0)) ? groups_at_a_time((int64_t)p.max_kv_len * p.d * 2, 160LL << 20) : 0;
     dim3 grid((unsigned)placed_workgroups(xcd_map, split ? 1 : 4, per_group, groups));
     const bool one_tile = (p.bq + p.b_sq - 1) / p.b_sq <= 32;
     // the four work items of a workgroup are consecutive items of one (sequence, kv head) group

@@ -52,9 +52,11 @@ int main()
                         }
                     ++cases;
                 }
-    // how many groups at a time: the largest power of two up to 8 whose rows stay below 160 MB
-    if (groups_at_a_time(8 << 20) != 8 || groups_at_a_time(32 << 20) != 4 || groups_at_a_time(64 << 20) != 2 ||
-        groups_at_a_time(256 << 20) != 1) {
+    // how many groups at a time: the largest power of two up to 8 whose rows stay within the budget
+    const int64_t mb = 1 << 20;
+    if (groups_at_a_time(8 * mb, 160 * mb) != 8 || groups_at_a_time(32 * mb, 160 * mb) != 4 || groups_at_a_time(64 * mb, 160 * mb) != 2 ||
+        groups_at_a_time(256 * mb, 160 * mb) != 1 || groups_at_a_time(128 * mb, 768 * mb) != 4 || groups_at_a_time(512 * mb, 768 * mb) != 1 ||
+        groups_at_a_time(96 * mb, 768 * mb) != 8) {
         std::printf("groups_at_a_time\n");
         return 1;
     }
