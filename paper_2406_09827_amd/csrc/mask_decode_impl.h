@@ -2,17 +2,16 @@
 // Alg. 1 per step over the current context, with bq = 1).
 //
 // With one query row the branch scoring is vector x gathered-rows work: bandwidth bound, no
-// use for the matrix cores.  One WAVE per (sequence, query head); the four waves of a
-// workgroup are the query heads of one KV group when Hq/Hkv = 4, so in the first round,
-// where all heads of a group score the same representative blocks, their loads meet in the
-// L1/L2 instead of going to HBM four times.
+// use for the matrix cores.  Two forms (template parameter SPLIT, chosen by the number of problems): one
+// WORKGROUP per (sequence, query head), or one WAVE per problem with the four waves of a workgroup being the
+// query heads of one KV group when Hq/Hkv = 4.  Either way the heads of a KV group run next to each other, so in
+// the first round, where they score the same representative blocks, their loads meet in the L1/L2 instead of
+// going to HBM four times.
 //   * a key row is read by D/8 lanes, 16 bytes each (a full 128-bit coalesced row segment),
 //     multiplied with v_dot2_f32_bf16 and summed over the lanes with DPP adds;
-//   * two stages of 16 (8 at large batch) row loads per lane alternate, so up to 32 KB per wave are in flight
-//     (a wave is alone on its SIMD at small batch, the memory pipeline has to be kept full
-//     from inside the wave);
-//   * scores -> per-wave LDS keys -> ordered threshold selection (once per wave, nothing
-//     redundant) -> the wave's private node list.  No workgroup barrier anywhere.
+//   * two stages of 8 row loads per lane alternate, so up to 16 KB per wave are in flight;
+//   * scores -> LDS keys -> ordered threshold selection -> the problem's node list (wave per problem: private to
+//     the wave, nothing redundant, no workgroup barrier anywhere);
 //   * with the first or the last block as representative, one child of every node has the
 //     node's own representative (left child / first block, right child / last block): its score is
 //     the score that selected the node, carried over as a key, and from the second round on only the
@@ -29,10 +28,10 @@ namespace hipattn {
 // SPLIT = false: one wave per (sequence, head), four independent problems per workgroup.
 // SPLIT = true : one workgroup per (sequence, head); the four waves score a quarter of the
 //                branches each (stage i goes to wave i % 4), meet at a barrier, run the selection
-//                redundantly and write a quarter of the survivors each.  Used at small batch,
-//                where one wave per SIMD cannot keep enough loads in flight.
+//                redundantly and write a quarter of the survivors each.  Used up to 8192 problems
+//                (see launch_e).
 template <int E, int BK, int D, int ROWS, bool PAGED, bool SPLIT>
-__global__ __launch_bounds__(kThreads, (E == 16 && ROWS == 8 && !SPLIT) ? 3 : 1) void mask_decode_kernel(KParams p, int xcd_map)
+__global__ __launch_bounds__(kThreads, E == 16 ? 3 : 1) void mask_decode_kernel(KParams p, int xcd_map)
 {
     constexpr int NB = 64 * E;
     constexpr int LPR = D / 8;        // lanes per key row
@@ -263,24 +262,21 @@ static hipError_t launch_r(const KParams &p, dim3 grid, int xcd_map, hipStream_t
     return hipGetLastError();
 }
 
-// Few problems (small batch): a workgroup per (sequence, head), four waves sharing the scoring, so
-// that enough loads are in flight per compute unit.  Many problems: a wave per problem; shallower
-// stages need fewer registers, so more waves fit a SIMD and hide each other's latency (including the
-// page-table lookups).
+// Up to 8192 problems: a workgroup per (sequence, head), four waves sharing the scoring, so that enough loads are in
+// flight per compute unit and the selection of one problem overlaps with the loads of the others.  Beyond that a wave
+// per problem (nothing computed twice, no barriers) is faster.  Measured with 32 query heads over 8 kv heads, k/bk =
+// 256, workgroup per problem against wave per problem: 2048 problems -8 %, 4096 -4 %, 8192 -1 to -4 %, 16384 +6 %,
+// 32768 +14 %.
 template <int BK, int D>
 static hipError_t launch_e(const KParams &p, hipStream_t st)
 {
     const int64_t problems = (int64_t)p.batch * p.hq;
-    if (problems < 2048) {
+    if (problems <= 8192) {
         const int64_t groups = (int64_t)p.batch * p.hkv;
         const int xcd_map = groups % 8 == 0 ? 1 : 0;
         return launch_r<BK, D, 8, true>(p, dim3((unsigned)problems), xcd_map, st);
     }
-    dim3 grid((unsigned)((problems + 3) / 4));
-    // Stages of 16 rows take about 240 registers: two waves per SIMD, two workgroups per compute unit.  With more than
-    // 512 workgroups, or with the selection state of kb > 256 on top, stages of 8 rows keep more waves resident.
-    if (grid.x > 512 || p.kb > 256) return launch_r<BK, D, 8, false>(p, grid, 0, st);
-    return launch_r<BK, D, 16, false>(p, grid, 0, st);
+    return launch_r<BK, D, 8, false>(p, dim3((unsigned)((problems + 3) / 4)), 0, st);
 }
 
 // One translation unit per (head dim, block width) instantiates this: WIDE = 4 or 8 scored rows per block, else 1 or 2.

@@ -72,7 +72,7 @@ def test_ensemble_samples_decode_and_generic(integer):
     wd = synth.Workload("ens_dec", 5, 8, 2, 128, 1, 30000, 256, 1, 2, "bf16", rho=0.9, ragged=(700, 30000), integer=integer, seed=705)
     _samples_match(wd, 3, 21, 5.0)
     _samples_match(synth.scaled(wd, page_size=16, seed=706), 2, 22, 5.0, rep_pos=2)
-    _samples_match(synth.scaled(wd, batch=600, kv_len=3000, ragged=(200, 3000), seed=707), 2, 23, 1.5)   # a wave per problem
+    _samples_match(synth.scaled(wd, batch=1100, kv_len=3000, ragged=(200, 3000), seed=707), 2, 23, 1.5)   # a wave per problem (8800 problems)
     wg = synth.Workload("ens_gen", 2, 2, 1, 64, 900, 900, 48, 16, 2, "fp32", rho=0.9, integer=integer, seed=708)
     _samples_match(wg, 3, 24, 3.0)
     _samples_match(synth.scaled(wd, seed=709), 2, 25, 5.0, flags=hipattn.FORCE_GENERIC)

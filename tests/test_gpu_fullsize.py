@@ -108,7 +108,7 @@ def test_c3_full_size(integer):
 
 
 def test_c5_ragged_paged_quarter_batch():
-    # the ragged, paged decode workload at a quarter of its batch (64 sequences, ~4.7 GB of KV)
+    # the ragged, paged decode workload at a quarter of its batch (64 sequences, ~4.7 GB of KV: 32-bit page offsets)
     w = synth.scaled(synth.C5, batch=64)
     agr, err = _fullsize(w, 24, seed=5)
     print(f"C5/4: agreement {agr:.6f}, max |dO| {err:.3e}")
@@ -116,8 +116,7 @@ def test_c5_ragged_paged_quarter_batch():
 
 def test_c5_full_batch():
     # the ragged, paged decode workload as bench.py launches it: 256 sequences = 8192 (sequence, head) problems
-    # (the shallow-stage, one-problem-per-wave decode kernels; ~18 GiB pools, 64-bit page offsets); only the
-    # sampled sequences' rows go to the host
+    # (a workgroup per problem; ~18 GiB pools, 64-bit page offsets); only the sampled sequences' rows go to the host
     agr, err = _fullsize(synth.C5, 32, seed=9)
     print(f"C5 full batch: agreement {agr:.6f}, max |dO| {err:.3e}")
 

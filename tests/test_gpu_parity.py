@@ -84,11 +84,24 @@ def test_chunk_of_queries_over_long_context(flags, q_len, bq):
 
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_decode_large_batch(integer):
-    # >= 4096 (sequence, head) problems selects the shallow-stage decode variant
-    w = synth.scaled(synth.C5, batch=128, kv_len=3000, ragged=(600, 3000), integer=integer)
+    # more than 8192 (sequence, head) problems select the wave-per-problem decode kernels (a workgroup per problem
+    # below that)
+    w = synth.scaled(synth.C5, batch=288, kv_len=3000, ragged=(600, 3000), integer=integer)
     rng = np.random.default_rng(2)
-    units = [(int(b), int(h), 0) for b, h in zip(rng.integers(0, 128, 300), rng.integers(0, 32, 300))]
+    units = [(int(b), int(h), 0) for b, h in zip(rng.integers(0, 288, 300), rng.integers(0, 32, 300))]
     U.run_case(w, 0, units=sorted(set(units)))
+
+
+@pytest.mark.parametrize("bk,d,k,page,T", [(1, 128, 64, 0, 1500), (2, 128, 512, 16, 1500), (1, 64, 512, 0, 1500), (4, 128, 1024, 64, 2500),
+                                           (8, 128, 2048, 0, 3000), (2, 64, 2048, 0, 2500)])
+def test_decode_wave_per_problem_variants(bk, d, k, page, T):
+    # the wave-per-problem kernels (more than 8192 problems) at every block width, both head dims, k/bk from 64 to
+    # 1024, contiguous and paged, ragged: 8320 problems of 8 query heads over one kv head, sampled against the oracle
+    w = synth.Workload("decode_wpp", 1040, 8, 1, d, 1, T, k, 1, bk, "bf16", rho=0.9, ragged=(T // 5, T), page_size=page,
+                       integer=True, seed=93)
+    rng = np.random.default_rng(bk * 100 + d)
+    units = sorted({(int(b), int(h), 0) for b, h in zip(rng.integers(0, 1040, 250), rng.integers(0, 8, 250))} | {(0, 0, 0), (1039, 7, 0)})
+    U.run_case(w, 0, units=units)
 
 
 @pytest.mark.parametrize("bk,d,k,hq,hkv", [(1, 128, 64, 4, 4), (4, 128, 1024, 8, 2), (2, 64, 256, 6, 2), (1, 64, 512, 4, 1),
