@@ -747,9 +747,10 @@ static hipError_t launch_mask_mfma_e(const KParams &p, int xcd_map, dim3 grid, b
             else HIPATTN_LAUNCH(mask_mfma_kernel_q64_split, 16);
         }
     } else if constexpr (MT == 1) {
-        // (contexts whose keys stay in the caches: beyond that the kernel waits on memory and the deeper
-        // prefetch of the register-staged variant is worth more than the third wave)
-        const bool direct = !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
+        // (up to 32 MB of keys per kv head, 128k tokens at head dim 128: beyond that the kernel waits on the memory
+        // side and the deeper prefetch of the register-staged variant makes up for the third wave - measured
+        // direct / staged at 48k 3.29 / 3.75 ms, 64k 4.81 / 5.43, 96k 9.20 / 9.58, 128k 14.72 / 15.00, 256k 41.9 / 41.8)
+        const bool direct = !p.page_table && (int64_t)p.max_kv_len * p.ks_r * 2 <= (32 << 20);
         const bool direct_paged = p.page_table && p.kb <= 256 && p.max_pages <= 1024 && one_sequence_per_workgroup &&
                                   (int64_t)p.max_kv_len * p.ks_r * 2 <= (16 << 20);
         if (direct_paged) hipLaunchKernelGGL((mask_mfma_kernel_q32_direct_paged<D, LB>), grid, block, 0, st, p, xcd_map);

@@ -566,14 +566,15 @@ def test_token_bank_in_host_memory():
 
 @pytest.mark.parametrize("integer", [True, False], ids=["int", "normal"])
 def test_direct_to_lds_variant_limits(integer):
-    # the mask kernel with direct-to-LDS loads serves contiguous K of up to 16 MB per kv head (64k keys at head dim 128):
-    # the largest context it takes, the first one it leaves to the register-staged kernel, a short last key block, list
-    # rounds (first / last representative), key sampling and a ragged batch
-    w = synth.Workload("direct_64k", 1, 4, 1, 128, 8192, 65536, 512, 32, 2, "bf16", rho=0.95, spike_every=8192,
+    # the mask kernel with direct-to-LDS loads serves contiguous K of up to 32 MB per kv head (128k keys at head dim
+    # 128): the largest context it takes, the first one it leaves to the register-staged kernel, 64k keys, a short last
+    # key block, list rounds (first / last representative), key sampling and a ragged batch
+    w = synth.Workload("direct_128k", 1, 4, 1, 128, 8192, 131072, 512, 32, 2, "bf16", rho=0.95, spike_every=8192,
                        integer=integer, seed=131)
     nqb = w.n_query_blocks
     units = [(0, h, qb) for h in range(4) for qb in (0, 1, 77, nqb // 2, nqb - 2, nqb - 1)]
     U.run_case(w, 0, units=units)
+    U.run_case(synth.scaled(w, kv_len=131072 + 64), 0, units=units)
     U.run_case(synth.scaled(w, kv_len=65536 + 64), 0, units=units)
     U.run_case(synth.scaled(w, kv_len=40001, q_len=9001), 0, units=[(0, h, qb) for h in range(4) for qb in (0, 100, 281)], rep_pos=2)
     U.run_case(synth.scaled(w, kv_len=30000, q_len=30000, bk=4, k=1024), 0,
